@@ -1,0 +1,175 @@
+"""fp64 CPU oracle for the full-vocabulary knowledge-distillation loss.
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain reference that the
+GPU library is checked against.  Only the tests, the smoke check and the
+`cpu_baseline` leg of the benchmark may import it; the product path never
+does.  It shares no code with the HIP kernels and imports nothing from the
+package.
+
+What it computes (paper, abstract and Sec. 3.2 "Efficient Communication via
+Hidden States"): on a student worker the teacher's final hidden states h_t are
+turned back into full-vocabulary logits through a frozen copy of the teacher
+output head, z_t = h_t . W_t, and compared with the student logits
+z_s = h_s . W_s under one of the divergences the paper names in Sec. 3.4
+(forward KL, reverse KL, Jensen-Shannon).  The paper's claim is that this is
+mathematically the same as standard logit-based distillation, so the oracle is
+the textbook definition with the logits fully materialised (row blocks only
+bound the RAM; they do not change the arithmetic of any row).
+
+The paper names the divergences without printing formulas.  Readings taken:
+  * p = softmax(z / tau) for BOTH models, natural logarithm, no tau^2 factor;
+  * FKL  = KL(p_t || p_s),  RKL = KL(p_s || p_t), per token;
+  * JSD(beta) = beta KL(p_t || M) + (1-beta) KL(p_s || M),
+    M = beta p_t + (1-beta) p_s   (generalised JSD of the GKD paper the
+    authors cite; beta=0.5 is the classic symmetric JSD);
+  * the loss is the masked mean over tokens: sum_t mask_t l_t / sum_t mask_t,
+    and is 0 with zero gradients when every token is masked;
+  * 0 log 0 := 0.
+Every function below is pinned by tests that do not call it to make their
+expected values (closed forms, library routines for special cases, finite
+differences, inequalities); see tests/test_oracle_pins.py.
+
+Gradients are the exact derivatives of that loss:
+  dL/dz_s[t,:] = mask_t / (n tau) * g_t,  with
+    FKL: g = p_s - p_t
+    RKL: g = p_s * ((log p_s - log p_t) - l_t)
+    JSD: g = (1-beta) p_s * ((log p_s - log M) - K_t),  K_t = KL(p_s || M)
+  grad_h_s = dz . W_s^T,   grad_W_s = h_s^T . dz        (Sec. 3.1, student backward)
+"""
+from __future__ import annotations
+
+import numpy as np
+
+FKL, RKL, JSD = 0, 1, 2
+KIND_NAMES = {FKL: "fkl", RKL: "rkl", JSD: "jsd"}
+
+# storage order of an output head: W_HV is the mathematical [H, V] array,
+# W_VH is its transpose [V, H] (the order lm_head.weight is kept in).
+W_HV, W_VH = 0, 1
+
+
+def _as_hv(W, w_layout):
+    """Return the head as the mathematical [H, V] fp64 array."""
+    W = np.asarray(W, dtype=np.float64)
+    if w_layout == W_HV:
+        return W
+    if w_layout == W_VH:
+        return W.T
+    raise ValueError("unknown w_layout")
+
+
+def logits(h, W, w_layout=W_HV):
+    """z = h . W, [T,H] x [H,V] -> [T,V] (Sec. 3.2: logit recomputation)."""
+    return np.asarray(h, dtype=np.float64) @ _as_hv(W, w_layout)
+
+
+def log_softmax(z, tau=1.0):
+    """Row-wise log softmax of z / tau, max-subtracted."""
+    u = np.asarray(z, dtype=np.float64) / float(tau)
+    u = u - u.max(axis=-1, keepdims=True)
+    return u - np.log(np.exp(u).sum(axis=-1, keepdims=True))
+
+
+def _xlogy_diff(p, la, lb):
+    """sum_v p * (la - lb) with the convention 0 * anything := 0."""
+    d = la - lb
+    term = np.where(p > 0.0, p * np.where(p > 0.0, d, 0.0), 0.0)
+    return term.sum(axis=-1)
+
+
+def divergence_rows(z_t, z_s, tau, kind, beta=0.5):
+    """Per-token divergence l[T] and g[T,V] = tau * d l_t / d z_s[t,:].
+
+    z_t, z_s: [T,V] raw logits.  Sec. 3.4 names the divergences; formulas are
+    the textbook ones stated in the module header.
+    """
+    lt = log_softmax(z_t, tau)
+    ls = log_softmax(z_s, tau)
+    pt = np.exp(lt)
+    ps = np.exp(ls)
+    if kind == FKL:
+        l = _xlogy_diff(pt, lt, ls)
+        g = ps - pt
+    elif kind == RKL:
+        l = _xlogy_diff(ps, ls, lt)
+        g = ps * ((ls - lt) - l[:, None])
+    elif kind == JSD:
+        if not (0.0 < beta < 1.0):
+            raise ValueError("JSD needs 0 < beta < 1")
+        lm = np.logaddexp(np.log(beta) + lt, np.log1p(-beta) + ls)
+        k_s = _xlogy_diff(ps, ls, lm)          # KL(p_s || M)
+        k_t = _xlogy_diff(pt, lt, lm)          # KL(p_t || M)
+        l = beta * k_t + (1.0 - beta) * k_s
+        g = (1.0 - beta) * ps * ((ls - lm) - k_s[:, None])
+    else:
+        raise ValueError("unknown kind")
+    return l, g
+
+
+def kd_loss_from_logits(z_t, z_s, mask=None, tau=1.0, kind=FKL, beta=0.5):
+    """Standard logit-based KD: masked-mean loss, per-token loss and dL/dz_s.
+
+    This is the computation the paper says hidden-state transfer must stay
+    equivalent to (Sec. 3.2, last sentence).
+    """
+    z_t = np.asarray(z_t, dtype=np.float64)
+    z_s = np.asarray(z_s, dtype=np.float64)
+    T = z_t.shape[0]
+    m = np.ones(T) if mask is None else (np.asarray(mask) != 0).astype(np.float64)
+    n = m.sum()
+    l, g = divergence_rows(z_t, z_s, tau, kind, beta)
+    if n == 0:
+        return 0.0, l, np.zeros_like(g)
+    loss = float((m * l).sum() / n)
+    dz = (m / (n * tau))[:, None] * g
+    return loss, l, dz
+
+
+def kd_loss_fwd_bwd(h_t, W_t, h_s, W_s, mask=None, tau=1.0, kind=FKL, beta=0.5,
+                    w_layout=W_HV, row_block=512):
+    """The whole hot path in fp64.
+
+    Returns dict(loss, per_token_loss[T], n, grad_h_s[T,H_s], grad_W_s) with
+    grad_W_s in the same storage order as W_s.  Rows are processed `row_block`
+    at a time so that only a [row_block, V] slab of logits exists at once.
+    """
+    h_t = np.asarray(h_t, dtype=np.float64)
+    h_s = np.asarray(h_s, dtype=np.float64)
+    Wt = _as_hv(W_t, w_layout)
+    Ws = _as_hv(W_s, w_layout)
+    T = h_t.shape[0]
+    if h_s.shape[0] != T or Wt.shape[1] != Ws.shape[1]:
+        raise ValueError("shape mismatch")
+    m = np.ones(T) if mask is None else (np.asarray(mask) != 0).astype(np.float64)
+    n = m.sum()
+    per_tok = np.empty(T)
+    grad_h = np.zeros_like(h_s)
+    grad_W = np.zeros_like(Ws)                       # [H_s, V]
+    for r0 in range(0, T, row_block):
+        r1 = min(T, r0 + row_block)
+        z_t = h_t[r0:r1] @ Wt
+        z_s = h_s[r0:r1] @ Ws
+        l, g = divergence_rows(z_t, z_s, tau, kind, beta)
+        per_tok[r0:r1] = l
+        if n > 0:
+            dz = (m[r0:r1] / (n * tau))[:, None] * g
+            grad_h[r0:r1] = dz @ Ws.T
+            grad_W += h_s[r0:r1].T @ dz
+    loss = float((m * per_tok).sum() / n) if n > 0 else 0.0
+    if w_layout == W_VH:
+        grad_W = np.ascontiguousarray(grad_W.T)
+    return dict(loss=loss, per_token_loss=per_tok, n=int(n),
+                grad_h_s=grad_h, grad_W_s=grad_W)
+
+
+def row_lse(h, W, tau=1.0, w_layout=W_HV, row_block=512):
+    """lse_t = log sum_v exp(z[t,v]/tau) for every row (used to check sampled
+    outputs of full-size problems one by one)."""
+    h = np.asarray(h, dtype=np.float64)
+    Whv = _as_hv(W, w_layout)
+    out = np.empty(h.shape[0])
+    for r0 in range(0, h.shape[0], row_block):
+        u = (h[r0:r0 + row_block] @ Whv) / float(tau)
+        mx = u.max(axis=-1)
+        out[r0:r0 + row_block] = mx + np.log(np.exp(u - mx[:, None]).sum(axis=-1))
+    return out
