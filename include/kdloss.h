@@ -1,0 +1,135 @@
+/*
+ * libkdloss - full-vocabulary knowledge-distillation loss, forward + backward,
+ * for one AMD MI355X (gfx950).
+ *
+ * The operation (KDFlow paper, abstract and Sec. 3.2 "Efficient Communication
+ * via Hidden States"): a student worker receives the teacher's final hidden
+ * states h_t [T,H_t] instead of teacher logits, rebuilds the full teacher
+ * logits with a frozen copy of the teacher output head,  z_t = h_t . W_t,
+ * and aligns the student's logits  z_s = h_s . W_s  to them with one of the
+ * divergences of Sec. 3.4 (forward KL, reverse KL, Jensen-Shannon).  The
+ * student's backward pass (Sec. 3.1, StudentActorGroup) then needs
+ * dL/dh_s and dL/dW_s.  This library is that computation and nothing else.
+ *
+ * Definitions (the paper names the divergences; these are the textbook forms
+ * it refers to, natural logarithm, p = softmax(z / tau) for both models):
+ *   FKL: l_t = KL(p_t || p_s)            RKL: l_t = KL(p_s || p_t)
+ *   JSD: l_t = beta KL(p_t || M) + (1-beta) KL(p_s || M),  M = beta p_t + (1-beta) p_s
+ *   n = sum_t mask_t,  loss = sum_t mask_t l_t / n   (0 when n == 0)
+ *   grad_h_s = dL/dz_s . W_s^T,   grad_W_s = h_s^T . dL/dz_s
+ * No tau^2 factor is applied.  Logits are never stored: they are produced
+ * vocabulary tile by vocabulary tile in registers, twice (three times for JSD).
+ *
+ * Conventions of every entry point
+ *  - plain C ABI; no exceptions, no global state, no allocation, no device
+ *    synchronisation.  The caller owns every buffer.
+ *  - all argument checks run on the host before anything touches the GPU, so
+ *    they can be exercised on a machine without one.
+ *  - work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
+ *    the default stream) and the call returns without waiting.
+ */
+#ifndef KDLOSS_H
+#define KDLOSS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  KD_OK = 0,
+  KD_ERR_NULL = 1,        /* a required pointer is NULL                          */
+  KD_ERR_SHAPE = 2,       /* T, H_t, H_s or V < 1, or beyond the supported range */
+  KD_ERR_ALIGN = 3,       /* pointer not 16-byte aligned, or H_t/H_s/V % 8 != 0  */
+  KD_ERR_PARAM = 4,       /* tau <= 0 or not finite, unknown enum, beta outside (0,1) for JSD */
+  KD_ERR_WORKSPACE = 5,   /* workspace_bytes smaller than kd_loss_workspace_size */
+  KD_ERR_UNSUPPORTED = 6, /* valid request this build does not implement         */
+  KD_ERR_LAUNCH = 7       /* the HIP runtime refused a launch (see hipGetLastError) */
+} kd_status;
+
+/* Sec. 3.4: built-in divergence metrics */
+typedef enum { KD_FKL = 0, KD_RKL = 1, KD_JSD = 2 } kd_kind;
+
+typedef enum { KD_BF16 = 0, KD_F32 = 1 } kd_dtype;
+
+/* Storage order of an output head W (mathematical shape [H, V]):
+ *   KD_W_HV: W[k * V + v]   (V contiguous)
+ *   KD_W_VH: W[v * H + k]   (H contiguous; the order lm_head.weight is kept in)
+ * The same order applies to W_t, W_s and grad_W_s. */
+typedef enum { KD_W_HV = 0, KD_W_VH = 1 } kd_wlayout;
+
+typedef struct {
+  int64_t T;            /* tokens (batch x sequence, flattened)                     */
+  int64_t H_t, H_s;     /* teacher / student hidden sizes, multiples of 8           */
+  int64_t V;            /* vocabulary size shared by both heads, multiple of 8      */
+  int32_t in_dtype;     /* kd_dtype of h_t, W_t, h_s, W_s                           */
+  int32_t grad_dtype;   /* kd_dtype of grad_h_s and grad_W_s                        */
+  int32_t w_layout;     /* kd_wlayout                                               */
+  int32_t kind;         /* kd_kind                                                  */
+  float tau;            /* temperature, > 0                                         */
+  float beta;           /* JSD mixing weight on the teacher term, 0 < beta < 1;
+                           ignored for FKL / RKL                                    */
+  int32_t accumulate_grad_W; /* 0: grad_W_s is overwritten. 1: added to (gradient
+                           accumulation over micro-batches, Table 3 caption)        */
+  int32_t reserved;     /* must be 0                                                */
+} kd_loss_params;
+
+/* Bytes of device workspace kd_loss_fwd_bwd needs for these parameters.
+ * Host only.  The size is O(T * V_c + H_s * V_c + T * H_s) for a vocabulary
+ * chunk V_c chosen by the library (a few thousand columns): it never grows
+ * like T * V.  Returns KD_OK or the status kd_loss_fwd_bwd would return for
+ * the same params. */
+kd_status kd_loss_workspace_size(const kd_loss_params* params, size_t* bytes);
+
+/* Forward + backward of the distillation loss (paper Sec. 3.2 and 3.4; student
+ * backward of Sec. 3.1).
+ *
+ *  h_t  [T, H_t]  device, read-only, row-major (H contiguous), in_dtype
+ *  W_t  head of the teacher, device, read-only, in_dtype, order w_layout
+ *  h_s  [T, H_s]  device, read-only
+ *  W_s  head of the student, device, read-only
+ *  mask [T] uint8 device, non-zero = token counts; NULL = every token counts
+ *  loss            device, one float: the masked-mean divergence
+ *  per_token_loss  device, [T] floats (l_t for every token, masked or not) or NULL
+ *  grad_h_s [T, H_s] device, grad_dtype; rows of masked tokens are exactly 0
+ *  grad_W_s device, grad_dtype, same order as W_s; overwritten or accumulated
+ *  workspace       device, 256-byte aligned, workspace_bytes >= the size query
+ *  hip_stream      hipStream_t
+ *
+ * Pointers must be 16-byte aligned.  Inputs must not alias outputs or the
+ * workspace.  Results are bitwise reproducible from call to call (no floating
+ * point atomics).  On any status other than KD_OK and KD_ERR_LAUNCH nothing
+ * was enqueued. */
+kd_status kd_loss_fwd_bwd(const kd_loss_params* params,
+                          const void* h_t, const void* W_t,
+                          const void* h_s, const void* W_s,
+                          const uint8_t* mask,
+                          float* loss, float* per_token_loss,
+                          void* grad_h_s, void* grad_W_s,
+                          void* workspace, size_t workspace_bytes,
+                          void* hip_stream);
+
+/* Forward only: loss and per-token loss, no gradients (the logit tiles are
+ * produced once; twice for JSD).  Same arguments and checks as above. */
+kd_status kd_loss_fwd(const kd_loss_params* params,
+                      const void* h_t, const void* W_t,
+                      const void* h_s, const void* W_s,
+                      const uint8_t* mask,
+                      float* loss, float* per_token_loss,
+                      void* workspace, size_t workspace_bytes,
+                      void* hip_stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char* kd_status_string(kd_status status);
+
+/* Number of kernels the last plan for these params launches and the vocabulary
+ * chunk it uses; for reports.  Either output pointer may be NULL. */
+kd_status kd_loss_plan_info(const kd_loss_params* params, int64_t* vocab_chunk,
+                            int64_t* n_launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KDLOSS_H */

@@ -1,0 +1,242 @@
+// C ABI of libkdloss: argument checks, workspace planning and the launch sequence.
+// All checks are host-only and happen before the first HIP call.
+#include "../../include/kdloss.h"
+#include "kd_launch.h"
+
+#include <cmath>
+#include <cstdlib>
+
+namespace {
+
+using kd::Problem;
+
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+struct Layout {
+  size_t rowinfo, row_loss, partials, h_sT, W_sT, dz, dzT, gh32, total;
+};
+
+kd_status check_params(const kd_loss_params* p) {
+  if (!p) return KD_ERR_NULL;
+  if (p->T < 1 || p->H_t < 1 || p->H_s < 1 || p->V < 1) return KD_ERR_SHAPE;
+  if (p->T > (1 << 22) || p->V > (1 << 24) || p->H_t > 65536 || p->H_s > 65536) return KD_ERR_SHAPE;
+  if (p->H_t % 8 || p->H_s % 8 || p->V % 8) return KD_ERR_ALIGN;
+  if (p->in_dtype != KD_BF16 && p->in_dtype != KD_F32) return KD_ERR_PARAM;
+  if (p->grad_dtype != KD_BF16 && p->grad_dtype != KD_F32) return KD_ERR_PARAM;
+  if (p->w_layout != KD_W_HV && p->w_layout != KD_W_VH) return KD_ERR_PARAM;
+  if (p->kind != KD_FKL && p->kind != KD_RKL && p->kind != KD_JSD) return KD_ERR_PARAM;
+  if (!(p->tau > 0.f) || !std::isfinite(p->tau)) return KD_ERR_PARAM;
+  if (p->kind == KD_JSD && !(p->beta > 0.f && p->beta < 1.f)) return KD_ERR_PARAM;
+  if (p->accumulate_grad_W != 0 && p->accumulate_grad_W != 1) return KD_ERR_PARAM;
+  if (p->reserved != 0) return KD_ERR_PARAM;
+  if (p->in_dtype != KD_BF16) return KD_ERR_UNSUPPORTED;
+  if (p->H_t % 64 || p->H_s % 64) return KD_ERR_UNSUPPORTED;   // k-steps are whole 64-element blocks
+  if (p->w_layout != KD_W_VH) return KD_ERR_UNSUPPORTED;
+  return KD_OK;
+}
+
+// Tile counts, vocabulary chunk and split factors.  Depends on the params only.
+void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward) {
+  q.T = (int)p->T; q.V = (int)p->V; q.H_s = (int)p->H_s; q.H_t = (int)p->H_t;
+  q.kind = p->kind; q.tau = p->tau; q.beta = p->beta;
+  q.grad_f32 = p->grad_dtype == KD_F32;
+  q.accumulate_grad_W = p->accumulate_grad_W;
+  q.n_cu = kd::kNumCU;
+  q.T_pad = (int)round_up(q.T, kd::kTileN);
+  q.n_tt = q.T_pad / kd::kTileN;
+  q.n_vt = (int)((q.V + kd::kTileM - 1) / kd::kTileM);
+  int ns = (q.n_cu + q.n_tt - 1) / q.n_tt;
+  if (ns > q.n_vt) ns = q.n_vt;
+  if (ns < 1) ns = 1;
+  q.n_split = ns;
+
+  // vocabulary chunk of the backward pass: the largest power of two (1024..16384 columns)
+  // whose [T_pad, V_c] bf16 staging buffer stays within 128 MiB
+  int64_t vc = 16384;
+  while (vc > 1024 && (int64_t)q.T_pad * vc * 2 > (128ll << 20)) vc >>= 1;
+  if (const char* e = std::getenv("KD_VOCAB_CHUNK")) {
+    const long v = std::atol(e);
+    if (v >= 256 && v <= (1 << 20)) vc = round_up(v, 256);
+  }
+  const int64_t v_all = round_up(q.V, 256);
+  if (vc > v_all) vc = v_all;
+  q.V_c = (int)vc;
+
+  // split-K of the grad_h_s product so that a chunk offers about one tile per CU
+  const int tiles_h = ((q.H_s + kd::kTileM - 1) / kd::kTileM) * q.n_tt;
+  int sk = q.n_cu / tiles_h;
+  if (sk < 1) sk = 1;
+  if (sk > 8) sk = 8;
+  while (sk > 1 && q.V_c / sk < 512) --sk;
+  const int steps_first = (int)(round_up(q.V < q.V_c ? q.V : q.V_c, 64) / 64);
+  if (sk > steps_first) sk = steps_first;
+  q.ksteps_h = (steps_first + sk - 1) / sk;
+  q.n_ksplit_h = (steps_first + q.ksteps_h - 1) / q.ksteps_h;   // every part is written by the first chunk
+
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = (size_t)round_up((int64_t)(off + bytes), 256); return o; };
+  L.rowinfo = take((size_t)q.T_pad * 16);
+  L.row_loss = take((size_t)q.T_pad * 4);
+  L.partials = take((size_t)q.n_split * 4 * 5 * q.T_pad * 4);
+  if (with_backward) {
+    L.h_sT = take((size_t)q.H_s * q.T_pad * 2);
+    L.W_sT = take((size_t)q.H_s * q.V_c * 2);
+    L.dz = take((size_t)q.T_pad * q.V_c * 2);
+    L.dzT = take((size_t)q.V_c * q.T_pad * 2);
+    L.gh32 = take((size_t)q.n_ksplit_h * q.T * q.H_s * 4);
+  } else {
+    L.h_sT = L.W_sT = L.dz = L.dzT = L.gh32 = off;
+  }
+  L.total = off;
+}
+
+void carve(Problem& q, const Layout& L, void* ws) {
+  char* b = static_cast<char*>(ws);
+  q.rowinfo = reinterpret_cast<float*>(b + L.rowinfo);
+  q.row_loss = reinterpret_cast<float*>(b + L.row_loss);
+  q.partials = reinterpret_cast<float*>(b + L.partials);
+  q.h_sT = b + L.h_sT;
+  q.W_sT = b + L.W_sT;
+  q.dz = b + L.dz;
+  q.dzT = b + L.dzT;
+  q.gh32 = reinterpret_cast<float*>(b + L.gh32);
+}
+
+#define KD_TRY(expr)                           \
+  do {                                         \
+    if ((expr) != hipSuccess) return KD_ERR_LAUNCH; \
+  } while (0)
+
+kd_status run_forward(const Problem& q, hipStream_t st) {
+  KD_TRY(kd::launch_stats(q, st));
+  KD_TRY(kd::launch_combine(q, st));
+  if (q.kind == KD_JSD) {
+    KD_TRY(kd::launch_jsd_rows(q, st));
+    KD_TRY(kd::launch_combine_jsd(q, st));
+  }
+  KD_TRY(kd::launch_finalize(q, st));
+  return KD_OK;
+}
+
+kd_status check_buffers(const kd_loss_params* params, const void* h_t, const void* W_t, const void* h_s,
+                        const void* W_s, const uint8_t* mask, float* loss, void* workspace,
+                        size_t workspace_bytes, bool backward, void* grad_h_s, void* grad_W_s,
+                        Problem& q, Layout& L) {
+  kd_status s = check_params(params);
+  if (s != KD_OK) return s;
+  if (!h_t || !W_t || !h_s || !W_s || !loss || !workspace) return KD_ERR_NULL;
+  if (backward && (!grad_h_s || !grad_W_s)) return KD_ERR_NULL;
+  if (!aligned16(h_t) || !aligned16(W_t) || !aligned16(h_s) || !aligned16(W_s)) return KD_ERR_ALIGN;
+  if (backward && (!aligned16(grad_h_s) || !aligned16(grad_W_s))) return KD_ERR_ALIGN;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return KD_ERR_ALIGN;
+  plan(params, q, L, backward);
+  if (workspace_bytes < L.total) return KD_ERR_WORKSPACE;
+  q.h_t = h_t; q.W_t = W_t; q.h_s = h_s; q.W_s = W_s; q.mask = mask;
+  q.loss = loss;
+  q.grad_h_s = grad_h_s; q.grad_W_s = grad_W_s;
+  carve(q, L, workspace);
+  return KD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+kd_status kd_loss_workspace_size(const kd_loss_params* params, size_t* bytes) {
+  if (!bytes) return KD_ERR_NULL;
+  kd_status s = check_params(params);
+  if (s != KD_OK) return s;
+  Problem q{};
+  Layout L{};
+  plan(params, q, L, true);
+  *bytes = L.total;
+  return KD_OK;
+}
+
+kd_status kd_loss_plan_info(const kd_loss_params* params, int64_t* vocab_chunk, int64_t* n_launches) {
+  kd_status s = check_params(params);
+  if (s != KD_OK) return s;
+  Problem q{};
+  Layout L{};
+  plan(params, q, L, true);
+  const int64_t chunks = (q.V + q.V_c - 1) / q.V_c;
+  if (vocab_chunk) *vocab_chunk = q.V_c;
+  if (n_launches) *n_launches = 3 + (q.kind == KD_JSD ? 2 : 0) + 1 + chunks * 4 + 1;
+  return KD_OK;
+}
+
+kd_status kd_loss_fwd(const kd_loss_params* params, const void* h_t, const void* W_t, const void* h_s,
+                      const void* W_s, const uint8_t* mask, float* loss, float* per_token_loss,
+                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Problem q{};
+  Layout L{};
+  kd_status s = check_buffers(params, h_t, W_t, h_s, W_s, mask, loss, workspace, workspace_bytes, false,
+                              nullptr, nullptr, q, L);
+  if (s != KD_OK) return s;
+  q.per_token_loss = per_token_loss;
+  return run_forward(q, static_cast<hipStream_t>(hip_stream));
+}
+
+kd_status kd_loss_fwd_bwd(const kd_loss_params* params, const void* h_t, const void* W_t, const void* h_s,
+                          const void* W_s, const uint8_t* mask, float* loss, float* per_token_loss,
+                          void* grad_h_s, void* grad_W_s, void* workspace, size_t workspace_bytes,
+                          void* hip_stream) {
+  Problem q{};
+  Layout L{};
+  kd_status s = check_buffers(params, h_t, W_t, h_s, W_s, mask, loss, workspace, workspace_bytes, true,
+                              grad_h_s, grad_W_s, q, L);
+  if (s != KD_OK) return s;
+  q.per_token_loss = per_token_loss;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+
+  s = run_forward(q, st);
+  if (s != KD_OK) return s;
+
+  // h_s^T [H_s][T_pad] once (token axis zero-padded): the K-contiguous operand of grad_W_s
+  KD_TRY(kd::launch_transpose(q.h_s, q.H_s, q.T, q.H_s, q.h_sT, q.T_pad, q.T_pad, st));
+
+  const size_t gsz = q.grad_f32 ? 4 : 2;
+  bool first = true;
+  for (int64_t v0 = 0; v0 < q.V; v0 += q.V_c) {
+    const int width = (int)((q.V - v0 < q.V_c) ? q.V - v0 : q.V_c);
+    KD_TRY(kd::launch_grad_chunk(q, (int)v0, width, st));
+    // W_s[chunk]^T [H_s][V_c]: the K-contiguous operand of grad_h_s
+    KD_TRY(kd::launch_transpose(static_cast<const char*>(q.W_s) + (size_t)v0 * q.H_s * 2, q.H_s, width, q.H_s,
+                                q.W_sT, q.V_c, (int)round_up(width, 64), st));
+    kd::GemmDesc gw{};   // grad_W_s[v][h] = sum_t h_sT[h][t] dzT[v][t]
+    gw.A = q.h_sT; gw.lda = q.T_pad; gw.M = q.H_s;
+    gw.B = q.dzT; gw.ldb = q.T_pad; gw.N = width;
+    gw.K = q.T_pad; gw.ksteps_per_split = 0;
+    gw.out = static_cast<char*>(q.grad_W_s) + (size_t)v0 * q.H_s * gsz;
+    gw.ldo = q.H_s; gw.out_split_stride = 0;
+    gw.out_f32 = q.grad_f32; gw.accumulate = q.accumulate_grad_W;
+    KD_TRY(kd::launch_gemm(gw, q.n_cu, st));
+    kd::GemmDesc gh{};   // grad_h_s[t][h] += sum_v W_sT[h][v] dz[t][v]
+    gh.A = q.W_sT; gh.lda = q.V_c; gh.M = q.H_s;
+    gh.B = q.dz; gh.ldb = q.V_c; gh.N = q.T;
+    gh.K = (int)round_up(width, 64); gh.ksteps_per_split = q.ksteps_h;
+    gh.out = q.gh32; gh.ldo = q.H_s; gh.out_split_stride = (int64_t)q.T * q.H_s;
+    gh.out_f32 = 1; gh.accumulate = first ? 0 : 1;
+    KD_TRY(kd::launch_gemm(gh, q.n_cu, st));
+    first = false;
+  }
+  KD_TRY(kd::launch_gradh_finish(q, st));
+  return KD_OK;
+}
+
+const char* kd_status_string(kd_status status) {
+  switch (status) {
+    case KD_OK: return "ok";
+    case KD_ERR_NULL: return "a required pointer is NULL";
+    case KD_ERR_SHAPE: return "T, H_t, H_s or V out of range";
+    case KD_ERR_ALIGN: return "pointer not 16-byte aligned or size not a multiple of 8";
+    case KD_ERR_PARAM: return "invalid tau, beta, enum value or flag";
+    case KD_ERR_WORKSPACE: return "workspace too small";
+    case KD_ERR_UNSUPPORTED: return "valid request not implemented by this build";
+    case KD_ERR_LAUNCH: return "HIP launch failed";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,663 @@
+// gfx950 kernels of libkdloss and their launchers.
+//
+// Pass structure (one call of kd_loss_fwd_bwd):
+//   stats    : logit tiles (student then teacher) -> online max / sum-exp / cross term per token
+//   combine  : merge partial statistics -> log-sum-exps, FKL / RKL row losses
+//   jsd_rows : (JSD only) logit tiles again -> KL(p_t||M), KL(p_s||M) per token
+//   finalize : n = sum mask, loss, per-row gradient scale mask/(n tau)
+//   per vocabulary chunk:
+//     grad   : logit tiles again -> dL/dz_s tile in bf16, stored both [T,Vc] and [Vc,T]
+//     gemm   : grad_W_s[chunk] = dz^T . h_s     and     grad_h_s += dz . W_s[chunk]
+//   gradh_finish : fp32 partial sums -> grad_h_s
+// All logarithms inside the kernels are base 2: a = z * log2(e)/tau.
+#include "kd_mfma.hpp"
+#include "kd_launch.h"
+
+namespace kd {
+
+// ------------------------------------------------------------------------------------------
+// work maps
+// ------------------------------------------------------------------------------------------
+
+// Workgroups are dealt to the 8 XCDs round-robin by workgroup id.  Renumber so
+// that consecutive logical ids sit on one XCD (and share its L2).
+__device__ __forceinline__ int xcd_logical_id(int b, int G) {
+  return (G % 8 == 0) ? (b % 8) * (G / 8) + b / 8 : b;
+}
+
+// Index q over an (na x nb) grid walked in (ba x bb) blocks, a fastest inside a block.
+__device__ __forceinline__ void block_decode(int q, int na, int ba, int bb, int& a, int& b) {
+  const int per = ba * bb;
+  const int blk = q / per, w = q - blk * per;
+  const int nblk_a = na / ba;
+  a = (blk % nblk_a) * ba + w % ba;
+  b = (blk / nblk_a) * bb + w / ba;
+}
+
+struct LogitArgs {
+  const bf16_t* W_s; const bf16_t* h_s; const bf16_t* W_t; const bf16_t* h_t;
+  int T, V, H_s, H_t;
+  int n_tt;            // token tiles of BN rows
+  int vt0, n_vt;       // vocabulary tiles [vt0, vt0 + n_vt) of BM rows handled by this launch
+  int n_split;         // stats kernels: vocabulary splits (grid = n_tt * n_split)
+  int ba, bb;          // block shape of the work map (ba | n_tt, bb | n_split or n_vt)
+  float c;             // log2(e) / tau
+  float beta;
+  int T_pad;
+  float* partials;     // stats: [n_split*4][5][T_pad];  jsd: [n_split*4][2][T_pad]
+  const f32x4* rowinfo;// [T_pad]: {lse2_t, lse2_s, mask/(n tau), row term}
+  bf16_t* dz;          // [T_pad][ldz]   chunk of dL/dz_s, vocabulary contiguous
+  bf16_t* dzT;         // [Vc][T_pad]    the same chunk, token contiguous
+  int ldz;
+};
+
+__device__ __forceinline__ WorkItem logit_item(const LogitArgs& a, int vt, int tt) {
+  WorkItem it;
+  it.A0 = a.W_s + (int64_t)vt * BM * a.H_s;
+  it.A1 = a.W_t + (int64_t)vt * BM * a.H_t;
+  it.B0 = a.h_s + (int64_t)tt * BN * a.H_s;
+  it.B1 = a.h_t + (int64_t)tt * BN * a.H_t;
+  it.a_rows = min(BM, a.V - vt * BM);
+  it.b_rows = min(BN, a.T - tt * BN);
+  it.nk0 = a.H_s / BK;
+  it.nk1 = a.H_t / BK;
+  it.m0 = vt * BM;
+  it.n0 = tt * BN;
+  it.aux = 0;
+  return it;
+}
+
+// One workgroup = one (token tile, vocabulary split); it walks the split's tiles in order.
+struct SplitWork {
+  const LogitArgs& a;
+  int tt, split, lo, cnt;
+  __device__ SplitWork(const LogitArgs& a_) : a(a_) {
+    const int L = xcd_logical_id(blockIdx.x, gridDim.x);
+    block_decode(L, a.n_tt, a.ba, a.bb, tt, split);
+    lo = (int)(((int64_t)split * a.n_vt) / a.n_split);
+    const int hi = (int)(((int64_t)(split + 1) * a.n_vt) / a.n_split);
+    cnt = hi - lo;
+  }
+  __device__ int n_items() const { return cnt; }
+  __device__ WorkItem item(int i) const { return logit_item(a, a.vt0 + lo + i, tt); }
+};
+
+// Persistent workgroups striding over the (token tile x vocabulary tile) grid of a chunk.
+struct ChunkWork {
+  const LogitArgs& a;
+  int L, G, n_tiles;
+  __device__ ChunkWork(const LogitArgs& a_) : a(a_) {
+    G = gridDim.x;
+    L = xcd_logical_id(blockIdx.x, G);
+    n_tiles = a.n_tt * a.n_vt;
+  }
+  __device__ int n_items() const { return L < n_tiles ? (n_tiles - L + G - 1) / G : 0; }
+  __device__ WorkItem item(int i) const {
+    int tt, vt;
+    block_decode(i * G + L, a.n_tt, a.ba, a.bb, tt, vt);
+    return logit_item(a, a.vt0 + vt, tt);
+  }
+};
+
+// ------------------------------------------------------------------------------------------
+// epilogues of the logit tiles
+// ------------------------------------------------------------------------------------------
+constexpr float NEG_BIG = -1.0e30f;
+constexpr float LN2 = 0.6931471805599453f;
+
+__device__ __forceinline__ float fexp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float flog2(float x) { return __builtin_amdgcn_logf(x); }
+
+// Rows of A beyond the vocabulary (last tile only) must not contribute: give them a
+// huge negative logit in both accumulators (their exp is 0, their difference is 0).
+__device__ __forceinline__ void mask_tail_rows(const WorkItem& it, AccTile& accS, AccTile& accT,
+                                               int wm, int lane) {
+  if (it.a_rows == BM) return;
+#pragma unroll
+  for (int mt = 0; mt < MI; ++mt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const bool ok = acc_m(wm, mt, r, lane) < it.a_rows;
+#pragma unroll
+      for (int nt = 0; nt < NI; ++nt) {
+        accS[mt][nt][r] = ok ? accS[mt][nt][r] : NEG_BIG;
+        accT[mt][nt][r] = ok ? accT[mt][nt][r] : NEG_BIG;
+      }
+    }
+}
+
+// Online log-sum-exp of both models plus the cross term of FKL / RKL.
+//   FKL: X = sum_v 2^(a_t - m_t) (z_t - z_s)      RKL: X = sum_v 2^(a_s - m_s) (z_s - z_t)
+template <int KIND>
+struct StatsEpi {
+  float m_t[NI], S_t[NI], m_s[NI], S_s[NI], X[NI];
+  float c;
+  int wm, wn, lane;
+  __device__ StatsEpi(float c_) : c(c_) {
+    lane = threadIdx.x & 63;
+    wm = (threadIdx.x >> 6) & 1;
+    wn = threadIdx.x >> 7;
+#pragma unroll
+    for (int nt = 0; nt < NI; ++nt) { m_t[nt] = NEG_BIG; m_s[nt] = NEG_BIG; S_t[nt] = 0.f; S_s[nt] = 0.f; X[nt] = 0.f; }
+  }
+  __device__ void begin_item(const WorkItem&) {}
+  __device__ void end_item(const WorkItem& it, AccTile& accS, AccTile& accT) {
+    mask_tail_rows(it, accS, accT, wm, lane);
+#pragma unroll
+    for (int nt = 0; nt < NI; ++nt) {
+      float tmax = NEG_BIG, smax = NEG_BIG;
+#pragma unroll
+      for (int mt = 0; mt < MI; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          tmax = fmaxf(tmax, accT[mt][nt][r]);
+          smax = fmaxf(smax, accS[mt][nt][r]);
+        }
+      const float nmt = fmaxf(m_t[nt], tmax * c);
+      const float nms = fmaxf(m_s[nt], smax * c);
+      const float sct = fexp2(m_t[nt] - nmt);
+      const float scs = fexp2(m_s[nt] - nms);
+      float st = S_t[nt] * sct, ss = S_s[nt] * scs;
+      float x = X[nt] * (KIND == 0 ? sct : scs);
+#pragma unroll
+      for (int mt = 0; mt < MI; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float zt = accT[mt][nt][r], zs = accS[mt][nt][r];
+          const float et = fexp2(fmaf(zt, c, -nmt));
+          const float es = fexp2(fmaf(zs, c, -nms));
+          st += et;
+          ss += es;
+          if (KIND == 0) x = fmaf(et, zt - zs, x);
+          if (KIND == 1) x = fmaf(es, zs - zt, x);
+        }
+      m_t[nt] = nmt; m_s[nt] = nms; S_t[nt] = st; S_s[nt] = ss; X[nt] = x;
+    }
+  }
+  __device__ void write(const LogitArgs& a, int tt, int split) const {
+    const int part = split * 4 + wm * 2 + (lane >> 5);
+    float* p = a.partials + (int64_t)part * 5 * a.T_pad;
+#pragma unroll
+    for (int nt = 0; nt < NI; ++nt) {
+      const int t = tt * BN + acc_n(wn, nt, lane);
+      p[0 * a.T_pad + t] = m_t[nt];
+      p[1 * a.T_pad + t] = S_t[nt];
+      p[2 * a.T_pad + t] = m_s[nt];
+      p[3 * a.T_pad + t] = S_s[nt];
+      p[4 * a.T_pad + t] = X[nt];
+    }
+  }
+};
+
+// JSD row sums with both log-sum-exps known:  A1 = sum p_t (l_t - l_m),  A2 = sum p_s (l_s - l_m)
+// (base-2 logs), M = beta p_t + (1 - beta) p_s.
+struct JsdEpi {
+  float A1[NI], A2[NI], Lt[NI], Ls[NI];
+  float c, beta;
+  int wm, wn, lane;
+  __device__ JsdEpi(const LogitArgs& a, int tt) : c(a.c), beta(a.beta) {
+    lane = threadIdx.x & 63;
+    wm = (threadIdx.x >> 6) & 1;
+    wn = threadIdx.x >> 7;
+#pragma unroll
+    for (int nt = 0; nt < NI; ++nt) {
+      const f32x4 ri = a.rowinfo[tt * BN + acc_n(wn, nt, lane)];
+      Lt[nt] = ri[0]; Ls[nt] = ri[1]; A1[nt] = 0.f; A2[nt] = 0.f;
+    }
+  }
+  __device__ void begin_item(const WorkItem&) {}
+  __device__ void end_item(const WorkItem& it, AccTile& accS, AccTile& accT) {
+    mask_tail_rows(it, accS, accT, wm, lane);
+    const float omb = 1.f - beta;
+#pragma unroll
+    for (int nt = 0; nt < NI; ++nt) {
+      float a1 = A1[nt], a2 = A2[nt];
+#pragma unroll
+      for (int mt = 0; mt < MI; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float lt = fmaf(accT[mt][nt][r], c, -Lt[nt]);
+          const float ls = fmaf(accS[mt][nt][r], c, -Ls[nt]);
+          const float pt = fexp2(lt), ps = fexp2(ls);
+          const float M = fmaf(beta, pt, omb * ps);
+          const float lm = M > 0.f ? flog2(M) : 0.f;
+          a1 = fmaf(pt, lt - lm, a1);
+          a2 = fmaf(ps, ls - lm, a2);
+        }
+      A1[nt] = a1; A2[nt] = a2;
+    }
+  }
+  __device__ void write(const LogitArgs& a, int tt, int split) const {
+    const int part = split * 4 + wm * 2 + (lane >> 5);
+    float* p = a.partials + (int64_t)part * 2 * a.T_pad;
+#pragma unroll
+    for (int nt = 0; nt < NI; ++nt) {
+      const int t = tt * BN + acc_n(wn, nt, lane);
+      p[0 * a.T_pad + t] = A1[nt];
+      p[1 * a.T_pad + t] = A2[nt];
+    }
+  }
+};
+
+// dL/dz_s tile.  rowinfo = {lse2_t, lse2_s, s = mask/(n tau), R}
+//   FKL: dz = s (p_s - p_t)
+//   RKL: dz = s p_s (ln2 (l_s - l_t) - R),           R = row loss
+//   JSD: dz = s (1-beta) p_s (ln2 (l_s - l_m) - R),  R = KL(p_s || M)
+template <int KIND>
+struct GradEpi {
+  const LogitArgs& a;
+  float Lt[NI], Ls[NI], sc[NI], R[NI];
+  int wm, wn, lane;
+  __device__ GradEpi(const LogitArgs& a_) : a(a_) {
+    lane = threadIdx.x & 63;
+    wm = (threadIdx.x >> 6) & 1;
+    wn = threadIdx.x >> 7;
+  }
+  __device__ void begin_item(const WorkItem& it) {
+#pragma unroll
+    for (int nt = 0; nt < NI; ++nt) {
+      const f32x4 ri = a.rowinfo[it.n0 + acc_n(wn, nt, lane)];
+      Lt[nt] = ri[0]; Ls[nt] = ri[1]; sc[nt] = ri[2]; R[nt] = ri[3];
+    }
+  }
+  __device__ void end_item(const WorkItem& it, AccTile& accS, AccTile& accT) {
+    const float c = a.c, beta = a.beta, omb = 1.f - a.beta;
+    const int mloc0 = it.m0 - a.vt0 * BM;      // vocabulary offset inside the chunk
+#pragma unroll
+    for (int nt = 0; nt < NI; ++nt) {
+      const int n = it.n0 + acc_n(wn, nt, lane);
+      const float s = KIND == 2 ? sc[nt] * omb : sc[nt];
+#pragma unroll
+      for (int mt = 0; mt < MI; ++mt)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int m = acc_m(wm, mt, 4 * q, lane);
+          const bool ok = m < it.a_rows;
+          bf16x4 o;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float lt = fmaf(accT[mt][nt][4 * q + i], c, -Lt[nt]);
+            const float ls = fmaf(accS[mt][nt][4 * q + i], c, -Ls[nt]);
+            const float ps = fexp2(ls);
+            float g;
+            if (KIND == 0) {
+              g = ps - fexp2(lt);
+            } else if (KIND == 1) {
+              g = ps * fmaf(LN2, ls - lt, -R[nt]);
+            } else {
+              const float M = fmaf(beta, fexp2(lt), omb * ps);
+              const float lm = M > 0.f ? flog2(M) : 0.f;
+              g = ps * fmaf(LN2, ls - lm, -R[nt]);
+            }
+            const float d = ok ? s * g : 0.f;
+            o[i] = (bf16_t)d;
+            a.dzT[(int64_t)(mloc0 + m + i) * a.T_pad + n] = o[i];
+          }
+          *(bf16x4*)(a.dz + (int64_t)n * a.ldz + mloc0 + m) = o;
+        }
+    }
+  }
+};
+
+// ------------------------------------------------------------------------------------------
+// logit kernels
+// ------------------------------------------------------------------------------------------
+#define KD_KERNEL __global__ __launch_bounds__(NTHREADS, 1)
+
+template <int KIND>
+KD_KERNEL void stats_kernel(const LogitArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  SplitWork work(a);
+  StatsEpi<KIND> epi(a.c);
+  tile_loop<2>(work, epi, a.H_s, a.H_t, a.H_s, a.H_t, smem);
+  epi.write(a, work.tt, work.split);
+}
+
+KD_KERNEL void jsd_rows_kernel(const LogitArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  SplitWork work(a);
+  JsdEpi epi(a, work.tt);
+  tile_loop<2>(work, epi, a.H_s, a.H_t, a.H_s, a.H_t, smem);
+  epi.write(a, work.tt, work.split);
+}
+
+template <int KIND>
+KD_KERNEL void grad_kernel(const LogitArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  ChunkWork work(a);
+  GradEpi<KIND> epi(a);
+  tile_loop<2>(work, epi, a.H_s, a.H_t, a.H_s, a.H_t, smem);
+}
+
+// ------------------------------------------------------------------------------------------
+// plain products for the backward pass:  out[n][m] (+)= sum_k A[m][k] B[n][k]
+// ------------------------------------------------------------------------------------------
+struct GemmArgs {
+  const bf16_t* A; const bf16_t* B;
+  int lda, ldb;
+  int M, N;            // valid rows of A / of B
+  int K;               // contraction length, a multiple of BK
+  int n_ksplit;        // split-K parts; part s writes out + s * out_split_stride
+  int ksteps;          // k-steps of BK per part
+  void* out; int64_t ldo; int64_t out_split_stride;   // in elements
+  int out_f32;         // 1: float, 0: bf16
+  int accumulate;      // 1: out += D
+  int n_mt, n_nt;
+};
+
+struct GemmWork {
+  const GemmArgs& a;
+  int L, G, n_tiles;
+  __device__ GemmWork(const GemmArgs& a_) : a(a_) {
+    G = gridDim.x;
+    L = xcd_logical_id(blockIdx.x, G);
+    n_tiles = a.n_mt * a.n_nt * a.n_ksplit;
+  }
+  __device__ int n_items() const { return L < n_tiles ? (n_tiles - L + G - 1) / G : 0; }
+  __device__ WorkItem item(int i) const {
+    const int q = i * G + L;
+    const int mt = q % a.n_mt, rest = q / a.n_mt;
+    const int nt = rest % a.n_nt, ks = rest / a.n_nt;
+    const int k0 = ks * a.ksteps * BK;
+    WorkItem it;
+    it.A0 = it.A1 = a.A + (int64_t)mt * BM * a.lda + k0;
+    it.B0 = it.B1 = a.B + (int64_t)nt * BN * a.ldb + k0;
+    it.a_rows = min(BM, a.M - mt * BM);
+    it.b_rows = min(BN, a.N - nt * BN);
+    it.nk0 = it.nk1 = min(a.ksteps, a.K / BK - ks * a.ksteps);
+    it.m0 = mt * BM;
+    it.n0 = nt * BN;
+    it.aux = ks;
+    return it;
+  }
+};
+
+struct StoreEpi {
+  const GemmArgs& a;
+  int wm, wn, lane;
+  __device__ StoreEpi(const GemmArgs& a_) : a(a_) {
+    lane = threadIdx.x & 63;
+    wm = (threadIdx.x >> 6) & 1;
+    wn = threadIdx.x >> 7;
+  }
+  __device__ void begin_item(const WorkItem&) {}
+  __device__ void end_item(const WorkItem& it, AccTile& acc, AccTile&) {
+#pragma unroll
+    for (int nt = 0; nt < NI; ++nt) {
+      const int nl = acc_n(wn, nt, lane);
+      if (nl >= it.b_rows) continue;
+      const int64_t row = (int64_t)(it.n0 + nl) * a.ldo + (int64_t)it.aux * a.out_split_stride;
+#pragma unroll
+      for (int mt = 0; mt < MI; ++mt)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int ml = acc_m(wm, mt, 4 * q, lane);
+          if (ml >= it.a_rows) continue;
+          f32x4 v = {acc[mt][nt][4 * q], acc[mt][nt][4 * q + 1], acc[mt][nt][4 * q + 2], acc[mt][nt][4 * q + 3]};
+          if (a.out_f32) {
+            f32x4* p = (f32x4*)((float*)a.out + row + it.m0 + ml);
+            if (a.accumulate) v += *p;
+            *p = v;
+          } else {
+            bf16x4* p = (bf16x4*)((bf16_t*)a.out + row + it.m0 + ml);
+            if (a.accumulate) {
+              const bf16x4 old = *p;
+#pragma unroll
+              for (int i = 0; i < 4; ++i) v[i] += (float)old[i];
+            }
+            bf16x4 o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[i] = (bf16_t)v[i];
+            *p = o;
+          }
+        }
+    }
+  }
+};
+
+KD_KERNEL void gemm_kernel(const GemmArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  GemmWork work(a);
+  StoreEpi epi(a);
+  tile_loop<1>(work, epi, a.lda, a.lda, a.ldb, a.ldb, smem);
+}
+
+// ------------------------------------------------------------------------------------------
+// small kernels
+// ------------------------------------------------------------------------------------------
+
+// Merge the partial statistics of one token; write log-sum-exps and, for FKL / RKL, the row loss.
+__global__ void combine_kernel(const float* partials, int n_parts, int T, int T_pad, int kind, float c,
+                               f32x4* rowinfo, float* row_loss) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= T_pad) return;
+  if (t >= T) {   // padding rows: probabilities evaluate to 0, gradient scale 0
+    rowinfo[t] = f32x4{1.0e30f, 1.0e30f, 0.f, 0.f};
+    row_loss[t] = 0.f;
+    return;
+  }
+  float Mt = NEG_BIG, Ms = NEG_BIG;
+  for (int p = 0; p < n_parts; ++p) {
+    const float* q = partials + (int64_t)p * 5 * T_pad + t;
+    Mt = fmaxf(Mt, q[0]);
+    Ms = fmaxf(Ms, q[2 * T_pad]);
+  }
+  float St = 0.f, Ss = 0.f, X = 0.f;
+  for (int p = 0; p < n_parts; ++p) {
+    const float* q = partials + (int64_t)p * 5 * T_pad + t;
+    const float wt = fexp2(q[0] - Mt), ws = fexp2(q[2 * T_pad] - Ms);
+    St = fmaf(q[1 * T_pad], wt, St);
+    Ss = fmaf(q[3 * T_pad], ws, Ss);
+    X = fmaf(q[4 * T_pad], kind == 0 ? wt : ws, X);
+  }
+  const float Lt = Mt + flog2(St), Ls = Ms + flog2(Ss);
+  float loss = 0.f;
+  if (kind == 0) loss = LN2 * (c * X / St - Lt + Ls);
+  if (kind == 1) loss = LN2 * (c * X / Ss - Ls + Lt);
+  rowinfo[t] = f32x4{Lt, Ls, 0.f, loss};
+  row_loss[t] = loss;
+}
+
+// JSD: merge the row sums.  row loss = ln2 (beta A1 + (1-beta) A2),  R = KL(p_s||M) = ln2 A2
+__global__ void combine_jsd_kernel(const float* partials, int n_parts, int T, int T_pad, float beta,
+                                   f32x4* rowinfo, float* row_loss) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= T) return;
+  float A1 = 0.f, A2 = 0.f;
+  for (int p = 0; p < n_parts; ++p) {
+    const float* q = partials + (int64_t)p * 2 * T_pad + t;
+    A1 += q[0];
+    A2 += q[T_pad];
+  }
+  f32x4 ri = rowinfo[t];
+  ri[3] = LN2 * A2;
+  rowinfo[t] = ri;
+  row_loss[t] = LN2 * (beta * A1 + (1.f - beta) * A2);
+}
+
+// One workgroup: n = sum mask, loss = sum mask l / n, per-row gradient scale mask / (n tau).
+__global__ void finalize_kernel(const uint8_t* mask, const float* row_loss, int T, float tau,
+                                f32x4* rowinfo, float* loss_out, float* per_token_out) {
+  __shared__ double s_sum[1024];
+  __shared__ int s_cnt[1024];
+  const int tid = threadIdx.x;
+  double acc = 0.0;
+  int cnt = 0;
+  for (int t = tid; t < T; t += 1024) {
+    const bool on = mask == nullptr || mask[t] != 0;
+    const float l = row_loss[t];
+    if (on) { acc += (double)l; ++cnt; }
+    if (per_token_out) per_token_out[t] = l;
+  }
+  s_sum[tid] = acc;
+  s_cnt[tid] = cnt;
+  __syncthreads();
+  for (int s = 512; s > 0; s >>= 1) {
+    if (tid < s) { s_sum[tid] += s_sum[tid + s]; s_cnt[tid] += s_cnt[tid + s]; }
+    __syncthreads();
+  }
+  const int n = s_cnt[0];
+  if (tid == 0) *loss_out = n > 0 ? (float)(s_sum[0] / (double)n) : 0.f;
+  const float scale = n > 0 ? 1.f / ((float)n * tau) : 0.f;
+  for (int t = tid; t < T; t += 1024) {
+    const bool on = mask == nullptr || mask[t] != 0;
+    rowinfo[t][2] = on ? scale : 0.f;
+  }
+}
+
+// dst[c][r] = src[r][c] for r < R, zero for R <= r < R_pad;  c < C.  64 x 64 tiles through LDS.
+__global__ void transpose_kernel(const bf16_t* src, int64_t ld_src, int R, int C,
+                                 bf16_t* dst, int64_t ld_dst, int R_pad) {
+  __shared__ bf16_t tile[64][66];
+  const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int i = ty; i < 64; i += 4) {
+    const int r = r0 + i, c = c0 + tx;
+    tile[i][tx] = (r < R && c < C) ? src[(int64_t)r * ld_src + c] : (bf16_t)0.f;
+  }
+  __syncthreads();
+  for (int i = ty; i < 64; i += 4) {
+    const int c = c0 + i, r = r0 + tx;
+    if (c < C && r < R_pad) dst[(int64_t)c * ld_dst + r] = tile[tx][i];
+  }
+}
+
+// grad_h_s = sum over split-K parts of the fp32 partial sums, converted to the output dtype.
+__global__ void gradh_finish_kernel(const float* parts, int n_parts, int64_t n, int out_f32, void* out) {
+  const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (i >= n) return;
+  f32x4 v = *(const f32x4*)(parts + i);
+  for (int p = 1; p < n_parts; ++p) v += *(const f32x4*)(parts + (int64_t)p * n + i);
+  if (out_f32) {
+    *(f32x4*)((float*)out + i) = v;
+  } else {
+    bf16x4 o;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) o[k] = (bf16_t)v[k];
+    *(bf16x4*)((bf16_t*)out + i) = o;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// launchers
+// ------------------------------------------------------------------------------------------
+static int largest_divisor_le(int n, int cap) {
+  for (int d = cap; d > 1; --d)
+    if (n % d == 0) return d;
+  return 1;
+}
+
+template <class Kern>
+static hipError_t launch_big(Kern kern, int grid, hipStream_t st, const void* args_ptr, size_t args_size) {
+  (void)args_size;
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
+  if (e != hipSuccess) return e;
+  void* params[] = {const_cast<void*>(args_ptr)};
+  return hipLaunchKernel((const void*)kern, dim3(grid), dim3(NTHREADS), params, SMEM_BYTES, st);
+}
+
+static LogitArgs make_logit_args(const Problem& p) {
+  LogitArgs a{};
+  a.W_s = (const bf16_t*)p.W_s; a.h_s = (const bf16_t*)p.h_s;
+  a.W_t = (const bf16_t*)p.W_t; a.h_t = (const bf16_t*)p.h_t;
+  a.T = p.T; a.V = p.V; a.H_s = p.H_s; a.H_t = p.H_t;
+  a.n_tt = p.n_tt;
+  a.c = 1.4426950408889634f / p.tau;
+  a.beta = p.beta;
+  a.T_pad = p.T_pad;
+  a.rowinfo = (const f32x4*)p.rowinfo;
+  return a;
+}
+
+hipError_t launch_stats(const Problem& p, hipStream_t st) {
+  LogitArgs a = make_logit_args(p);
+  a.vt0 = 0; a.n_vt = p.n_vt; a.n_split = p.n_split;
+  a.ba = largest_divisor_le(p.n_tt, 4);
+  a.bb = largest_divisor_le(p.n_split, 8);
+  a.partials = p.partials;
+  const int grid = p.n_tt * p.n_split;
+  switch (p.kind) {
+    case 0: return launch_big(stats_kernel<0>, grid, st, &a, sizeof(a));
+    case 1: return launch_big(stats_kernel<1>, grid, st, &a, sizeof(a));
+    default: return launch_big(stats_kernel<2>, grid, st, &a, sizeof(a));
+  }
+}
+
+hipError_t launch_jsd_rows(const Problem& p, hipStream_t st) {
+  LogitArgs a = make_logit_args(p);
+  a.vt0 = 0; a.n_vt = p.n_vt; a.n_split = p.n_split;
+  a.ba = largest_divisor_le(p.n_tt, 4);
+  a.bb = largest_divisor_le(p.n_split, 8);
+  a.partials = p.partials;
+  return launch_big(jsd_rows_kernel, p.n_tt * p.n_split, st, &a, sizeof(a));
+}
+
+hipError_t launch_combine(const Problem& p, hipStream_t st) {
+  const int n_parts = p.n_split * 4;
+  hipLaunchKernelGGL(combine_kernel, dim3((p.T_pad + 255) / 256), dim3(256), 0, st, p.partials, n_parts, p.T,
+                     p.T_pad, p.kind, 1.4426950408889634f / p.tau, (f32x4*)p.rowinfo, p.row_loss);
+  return hipGetLastError();
+}
+
+hipError_t launch_combine_jsd(const Problem& p, hipStream_t st) {
+  const int n_parts = p.n_split * 4;
+  hipLaunchKernelGGL(combine_jsd_kernel, dim3((p.T + 255) / 256), dim3(256), 0, st, p.partials, n_parts, p.T,
+                     p.T_pad, p.beta, (f32x4*)p.rowinfo, p.row_loss);
+  return hipGetLastError();
+}
+
+hipError_t launch_finalize(const Problem& p, hipStream_t st) {
+  hipLaunchKernelGGL(finalize_kernel, dim3(1), dim3(1024), 0, st, p.mask, p.row_loss, p.T, p.tau,
+                     (f32x4*)p.rowinfo, p.loss, p.per_token_loss);
+  return hipGetLastError();
+}
+
+hipError_t launch_grad_chunk(const Problem& p, int v0, int width, hipStream_t st) {
+  LogitArgs a = make_logit_args(p);
+  a.vt0 = v0 / BM;
+  a.n_vt = (width + BM - 1) / BM;
+  a.ba = largest_divisor_le(p.n_tt, 4);
+  a.bb = largest_divisor_le(a.n_vt, 8);
+  a.dz = (bf16_t*)p.dz; a.dzT = (bf16_t*)p.dzT; a.ldz = p.V_c;
+  const int tiles = p.n_tt * a.n_vt;
+  int grid = tiles < p.n_cu ? tiles : p.n_cu;
+  switch (p.kind) {
+    case 0: return launch_big(grad_kernel<0>, grid, st, &a, sizeof(a));
+    case 1: return launch_big(grad_kernel<1>, grid, st, &a, sizeof(a));
+    default: return launch_big(grad_kernel<2>, grid, st, &a, sizeof(a));
+  }
+}
+
+hipError_t launch_transpose(const void* src, int64_t ld_src, int R, int C, void* dst, int64_t ld_dst, int R_pad,
+                            hipStream_t st) {
+  dim3 grid((R_pad + 63) / 64, (C + 63) / 64);
+  hipLaunchKernelGGL(transpose_kernel, grid, dim3(256), 0, st, (const bf16_t*)src, ld_src, R, C, (bf16_t*)dst,
+                     ld_dst, R_pad);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm(const GemmDesc& d, int n_cu, hipStream_t st) {
+  GemmArgs a{};
+  a.A = (const bf16_t*)d.A; a.B = (const bf16_t*)d.B;
+  a.lda = d.lda; a.ldb = d.ldb; a.M = d.M; a.N = d.N; a.K = d.K;
+  const int ksteps_total = d.K / BK;
+  a.ksteps = d.ksteps_per_split > 0 ? d.ksteps_per_split : ksteps_total;
+  a.n_ksplit = (ksteps_total + a.ksteps - 1) / a.ksteps;     // every part has at least one k-step
+  a.out = d.out; a.ldo = d.ldo; a.out_split_stride = d.out_split_stride;
+  a.out_f32 = d.out_f32; a.accumulate = d.accumulate;
+  a.n_mt = (d.M + BM - 1) / BM;
+  a.n_nt = (d.N + BN - 1) / BN;
+  const int tiles = a.n_mt * a.n_nt * a.n_ksplit;
+  const int grid = tiles < n_cu ? tiles : n_cu;
+  return launch_big(gemm_kernel, grid, st, &a, sizeof(a));
+}
+
+hipError_t launch_gradh_finish(const Problem& p, hipStream_t st) {
+  const int64_t n = (int64_t)p.T * p.H_s;
+  const int64_t threads = (n + 3) / 4;
+  hipLaunchKernelGGL(gradh_finish_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, p.gh32,
+                     p.n_ksplit_h, n, p.grad_f32, p.grad_h_s);
+  return hipGetLastError();
+}
+
+}  // namespace kd

@@ -1,0 +1,60 @@
+// Host-side interface between the C ABI layer and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime_api.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace kd {
+
+constexpr int kNumCU = 256;            // MI355X: 8 XCDs x 32 CUs; persistent grids are sized for it
+constexpr int kTileM = 128;            // vocabulary rows per logit tile
+constexpr int kTileN = 256;            // token rows per logit tile
+
+// Everything a launch needs, resolved by the planner in kd_api.hip.
+struct Problem {
+  int T, V, H_s, H_t;
+  int kind;
+  float tau, beta;
+  int grad_f32;
+  int accumulate_grad_W;
+  const void *h_t, *W_t, *h_s, *W_s;
+  const uint8_t* mask;
+  float* loss;
+  float* per_token_loss;
+  void *grad_h_s, *grad_W_s;
+  // plan
+  int T_pad, n_tt, n_vt, n_split, V_c, n_ksplit_h, ksteps_h, n_cu;
+  // workspace carve-up
+  float* rowinfo;      // [T_pad][4]
+  float* row_loss;     // [T_pad]
+  float* partials;     // [n_split*4][5][T_pad]
+  void* h_sT;          // bf16 [H_s][T_pad]
+  void* W_sT;          // bf16 [H_s][V_c]
+  void* dz;            // bf16 [T_pad][V_c]
+  void* dzT;           // bf16 [V_c][T_pad]
+  float* gh32;         // [n_ksplit_h][T][H_s]
+};
+
+// out[n][m] (+)= sum_k A[m][k] B[n][k]; A is [M][lda], B is [N][ldb], both K-contiguous bf16.
+struct GemmDesc {
+  const void *A, *B;
+  int lda, ldb, M, N;
+  int K;                  // multiple of 64
+  int ksteps_per_split;   // split-K: k-steps of 64 per part (0 = no split); part s writes out + s * out_split_stride
+  void* out;
+  int64_t ldo, out_split_stride;
+  int out_f32, accumulate;
+};
+
+hipError_t launch_stats(const Problem& p, hipStream_t st);
+hipError_t launch_combine(const Problem& p, hipStream_t st);
+hipError_t launch_jsd_rows(const Problem& p, hipStream_t st);
+hipError_t launch_combine_jsd(const Problem& p, hipStream_t st);
+hipError_t launch_finalize(const Problem& p, hipStream_t st);
+hipError_t launch_grad_chunk(const Problem& p, int v0, int width, hipStream_t st);
+hipError_t launch_transpose(const void* src, int64_t ld_src, int R, int C, void* dst, int64_t ld_dst, int R_pad,
+                            hipStream_t st);
+hipError_t launch_gemm(const GemmDesc& d, int n_cu, hipStream_t st);
+hipError_t launch_gradh_finish(const Problem& p, hipStream_t st);
+
+}  // namespace kd

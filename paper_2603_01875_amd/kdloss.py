@@ -1,0 +1,162 @@
+"""ctypes binding of libkdloss (see include/kdloss.h for the contract).
+
+Argument marshalling only: every step of the computation runs in the HIP
+kernels of the shared library.  torch is used to own device memory and to name
+the stream.  There is no fallback: if the library has not been built, loading
+fails with an error that says how to build it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+FKL, RKL, JSD = 0, 1, 2
+BF16, F32 = 0, 1
+W_HV, W_VH = 0, 1
+
+KD_OK = 0
+STATUS_NAMES = {0: "KD_OK", 1: "KD_ERR_NULL", 2: "KD_ERR_SHAPE", 3: "KD_ERR_ALIGN", 4: "KD_ERR_PARAM",
+                5: "KD_ERR_WORKSPACE", 6: "KD_ERR_UNSUPPORTED", 7: "KD_ERR_LAUNCH"}
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "libkdloss.so")
+_lib = None
+
+
+class KdLossParams(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_int64), ("H_t", ctypes.c_int64), ("H_s", ctypes.c_int64), ("V", ctypes.c_int64),
+                ("in_dtype", ctypes.c_int32), ("grad_dtype", ctypes.c_int32), ("w_layout", ctypes.c_int32),
+                ("kind", ctypes.c_int32), ("tau", ctypes.c_float), ("beta", ctypes.c_float),
+                ("accumulate_grad_W", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class KdLossError(RuntimeError):
+    def __init__(self, status):
+        self.status = int(status)
+        msg = lib().kd_status_string(self.status).decode()
+        super().__init__(f"{STATUS_NAMES.get(self.status, self.status)}: {msg}")
+
+
+def lib():
+    """The loaded shared library (loads on first use; never falls back to anything else)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} is missing: build it with "
+                               "`python -c 'import __graft_entry__ as g; g.build()'` "
+                               "or paper_2603_01875_amd/csrc/build.sh")
+        L = ctypes.CDLL(_LIB_PATH)
+        P = ctypes.POINTER(KdLossParams)
+        vp = ctypes.c_void_p
+        L.kd_loss_workspace_size.argtypes = [P, ctypes.POINTER(ctypes.c_size_t)]
+        L.kd_loss_workspace_size.restype = ctypes.c_int
+        L.kd_loss_plan_info.argtypes = [P, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]
+        L.kd_loss_plan_info.restype = ctypes.c_int
+        L.kd_loss_fwd_bwd.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.kd_loss_fwd_bwd.restype = ctypes.c_int
+        L.kd_loss_fwd.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.kd_loss_fwd.restype = ctypes.c_int
+        L.kd_status_string.argtypes = [ctypes.c_int]
+        L.kd_status_string.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def make_params(T, H_t, H_s, V, kind=FKL, tau=1.0, beta=0.5, in_dtype=BF16, grad_dtype=None,
+                w_layout=W_VH, accumulate_grad_W=False):
+    if grad_dtype is None:
+        grad_dtype = in_dtype
+    return KdLossParams(int(T), int(H_t), int(H_s), int(V), int(in_dtype), int(grad_dtype), int(w_layout),
+                        int(kind), float(tau), float(beta), int(bool(accumulate_grad_W)), 0)
+
+
+def kd_loss_workspace_size(params: KdLossParams) -> int:
+    n = ctypes.c_size_t(0)
+    st = lib().kd_loss_workspace_size(ctypes.byref(params), ctypes.byref(n))
+    if st != KD_OK:
+        raise KdLossError(st)
+    return int(n.value)
+
+
+def kd_loss_plan_info(params: KdLossParams):
+    vc, nl = ctypes.c_int64(0), ctypes.c_int64(0)
+    st = lib().kd_loss_plan_info(ctypes.byref(params), ctypes.byref(vc), ctypes.byref(nl))
+    if st != KD_OK:
+        raise KdLossError(st)
+    return int(vc.value), int(nl.value)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def kd_loss_fwd_bwd_raw(params, h_t, W_t, h_s, W_s, mask, loss, per_token_loss, grad_h_s, grad_W_s,
+                        workspace, stream=None):
+    """Thin call: all tensors are caller-allocated torch CUDA tensors (or None where allowed)."""
+    import torch
+    s = torch.cuda.current_stream().cuda_stream if stream is None else stream
+    st = lib().kd_loss_fwd_bwd(ctypes.byref(params), _ptr(h_t), _ptr(W_t), _ptr(h_s), _ptr(W_s), _ptr(mask),
+                               _ptr(loss), _ptr(per_token_loss), _ptr(grad_h_s), _ptr(grad_W_s),
+                               _ptr(workspace), ctypes.c_size_t(workspace.numel() * workspace.element_size()),
+                               ctypes.c_void_p(s))
+    if st != KD_OK:
+        raise KdLossError(st)
+
+
+def kd_loss_fwd_raw(params, h_t, W_t, h_s, W_s, mask, loss, per_token_loss, workspace, stream=None):
+    import torch
+    s = torch.cuda.current_stream().cuda_stream if stream is None else stream
+    st = lib().kd_loss_fwd(ctypes.byref(params), _ptr(h_t), _ptr(W_t), _ptr(h_s), _ptr(W_s), _ptr(mask),
+                           _ptr(loss), _ptr(per_token_loss), _ptr(workspace),
+                           ctypes.c_size_t(workspace.numel() * workspace.element_size()), ctypes.c_void_p(s))
+    if st != KD_OK:
+        raise KdLossError(st)
+
+
+def alloc_workspace(params, device="cuda"):
+    import torch
+    n = kd_loss_workspace_size(params)
+    return torch.empty((n + 255) // 256 * 256, dtype=torch.uint8, device=device)
+
+
+def kd_loss_fwd_bwd(h_t, W_t, h_s, W_s, mask=None, tau=1.0, kind=FKL, beta=0.5, w_layout=W_VH,
+                    grad_dtype=None, workspace=None, grad_W_s=None, accumulate_grad_W=False,
+                    want_per_token=True):
+    """Convenience wrapper: allocates outputs (and the workspace unless given) and calls the library.
+
+    h_t [T,H_t], h_s [T,H_s]; W_t, W_s in `w_layout` ([V,H] for W_VH).  Returns a dict of CUDA tensors.
+    """
+    import torch
+    in_dtype = BF16 if h_t.dtype == torch.bfloat16 else F32
+    T, H_t = h_t.shape
+    H_s = h_s.shape[1]
+    V = W_t.shape[0] if w_layout == W_VH else W_t.shape[1]
+    if grad_dtype is None:
+        grad_dtype = in_dtype
+    p = make_params(T, H_t, H_s, V, kind, tau, beta, in_dtype, grad_dtype, w_layout, accumulate_grad_W)
+    tdt = torch.bfloat16 if grad_dtype == BF16 else torch.float32
+    dev = h_t.device
+    if workspace is None:
+        workspace = alloc_workspace(p, dev)
+    loss = torch.empty(1, dtype=torch.float32, device=dev)
+    ptl = torch.empty(T, dtype=torch.float32, device=dev) if want_per_token else None
+    grad_h = torch.empty((T, H_s), dtype=tdt, device=dev)
+    if grad_W_s is None:
+        grad_W_s = torch.empty_like(W_s, dtype=tdt)
+    kd_loss_fwd_bwd_raw(p, h_t, W_t, h_s, W_s, mask, loss, ptl, grad_h, grad_W_s, workspace)
+    return dict(loss=loss, per_token_loss=ptl, grad_h_s=grad_h, grad_W_s=grad_W_s, workspace=workspace)
+
+
+def kd_loss_fwd(h_t, W_t, h_s, W_s, mask=None, tau=1.0, kind=FKL, beta=0.5, w_layout=W_VH, workspace=None):
+    import torch
+    in_dtype = BF16 if h_t.dtype == torch.bfloat16 else F32
+    T, H_t = h_t.shape
+    H_s = h_s.shape[1]
+    V = W_t.shape[0] if w_layout == W_VH else W_t.shape[1]
+    p = make_params(T, H_t, H_s, V, kind, tau, beta, in_dtype, in_dtype, w_layout)
+    dev = h_t.device
+    if workspace is None:
+        workspace = alloc_workspace(p, dev)
+    loss = torch.empty(1, dtype=torch.float32, device=dev)
+    ptl = torch.empty(T, dtype=torch.float32, device=dev)
+    kd_loss_fwd_raw(p, h_t, W_t, h_s, W_s, mask, loss, ptl, workspace)
+    return dict(loss=loss, per_token_loss=ptl)

@@ -1,0 +1,92 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every
+symbol the header declares, and rejects bad arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2603_01875_amd import kdloss as K
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    src = open(os.path.join(ROOT, "include", "kdloss.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(kd_[a-z_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_symbols()
+    assert {"kd_loss_workspace_size", "kd_loss_fwd_bwd", "kd_loss_fwd", "kd_status_string",
+            "kd_loss_plan_info"} <= set(names)
+    L = K.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_struct_layout_matches_header():
+    assert ctypes.sizeof(K.KdLossParams) == 4 * 8 + 8 * 4
+
+
+def test_status_strings():
+    for s in range(8):
+        assert len(K.lib().kd_status_string(s)) > 0
+
+
+def _ws(**kw):
+    base = dict(T=4096, H_t=4096, H_s=1024, V=151936)
+    base.update(kw)
+    return K.make_params(**base)
+
+
+def test_workspace_is_far_below_T_times_V():
+    p = _ws()
+    n = K.kd_loss_workspace_size(p)
+    vc, launches = K.kd_loss_plan_info(p)
+    assert n < 0.35 * 2 * 4096 * 151936           # never a [T, V] buffer
+    assert vc % 256 == 0 and vc <= 16384 and launches > 0
+    # long-sequence workload: chunk shrinks so the staging buffers stay bounded
+    p5 = K.make_params(32768, 5120, 4096, 151936, kind=K.JSD, beta=0.1)
+    n5 = K.kd_loss_workspace_size(p5)
+    assert n5 < 0.2 * 2 * 32768 * 151936
+    # the footnote's full-logit volume (128 x 4096 x 151936 bf16) is ~160 GB; ours is ~1000x smaller
+    assert 128 * 4096 * 151936 * 2 / n > 300
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(T=0), 2), (dict(V=-8), 2), (dict(H_t=100), 3), (dict(V=151937), 3),
+    (dict(tau=0.0), 4), (dict(tau=float("nan")), 4), (dict(kind=7), 4),
+    (dict(kind=K.JSD, beta=0.0), 4), (dict(kind=K.JSD, beta=1.0), 4), (dict(in_dtype=5), 4),
+    (dict(w_layout=K.W_HV), 6), (dict(H_s=72), 6),
+])
+def test_bad_params_are_rejected(kw, status):
+    with pytest.raises(K.KdLossError) as e:
+        K.kd_loss_workspace_size(_ws(**kw))
+    assert e.value.status == status
+
+
+def test_beta_ignored_for_kl():
+    K.kd_loss_workspace_size(_ws(kind=K.FKL, beta=5.0))
+
+
+def test_pointer_checks_run_before_any_gpu_work():
+    # fake, never dereferenced addresses: every call must fail on the host
+    p = _ws()
+    L = K.lib()
+    n = K.kd_loss_workspace_size(p)
+    good = [ctypes.c_void_p(0x1000 * (i + 1)) for i in range(10)]
+
+    def call(args, ws_bytes=n):
+        return L.kd_loss_fwd_bwd(ctypes.byref(p), *args, ctypes.c_size_t(ws_bytes), None)
+
+    for i in (0, 1, 2, 3, 5, 7, 8, 9):          # required pointers (mask=4, per_token=6 may be NULL)
+        a = list(good); a[i] = None
+        assert call(a) == 1, i
+    a = list(good); a[0] = ctypes.c_void_p(0x1008)
+    assert call(a) == 3
+    a = list(good); a[9] = ctypes.c_void_p(0x1010)  # workspace needs 256-byte alignment
+    assert call(a) == 3
+    assert call(good, n - 1) == 5
+    assert L.kd_loss_fwd_bwd(None, *good, ctypes.c_size_t(n), None) == 1
