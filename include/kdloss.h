@@ -129,6 +129,24 @@ const char* kd_status_string(kd_status status);
 kd_status kd_loss_plan_info(const kd_loss_params* params, int64_t* vocab_chunk,
                             int64_t* n_launches);
 
+/* Benchmark aid (not part of the method): per-kernel timing without a profiler.
+ * While a hook is set on the calling thread, every launch of the selected kernel
+ * family made by kd_loss_fwd / kd_loss_fwd_bwd on that thread is bracketed by
+ * hipEventRecord(events[2i]) before and hipEventRecord(events[2i+1]) after it, on the
+ * call's stream, i counting launches since the hook was set, while 2i+1 < n_events.
+ * `events` is a host array of hipEvent_t owned by the caller, which must outlive the
+ * hook.  which < 0 clears the hook.  Host only; touches no device memory. */
+typedef enum {
+  KD_PROF_STATS = 0,        /* logit tiles + online log-sum-exp (one launch per call)   */
+  KD_PROF_JSD_ROWS = 1,     /* JSD row pass (one launch per call, JSD only)             */
+  KD_PROF_GRAD = 2,         /* logit tiles + dL/dz_s epilogue (one launch per chunk)    */
+  KD_PROF_GEMM_GRAD_W = 3,  /* grad_W_s product (one launch per chunk)                  */
+  KD_PROF_GEMM_GRAD_H = 4   /* grad_h_s product (one launch per chunk)                  */
+} kd_prof_kernel;
+kd_status kd_loss_profile_hook(int which, void** events, int n_events);
+/* Pairs recorded since the hook was set. */
+int kd_loss_profile_count(void);
+
 #ifdef __cplusplus
 }
 #endif

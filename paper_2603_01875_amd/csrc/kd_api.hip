@@ -103,16 +103,48 @@ void carve(Problem& q, const Layout& L, void* ws) {
   q.gh32 = reinterpret_cast<float*>(b + L.gh32);
 }
 
+// Benchmark aid: bracket the launches of one kernel family with caller-supplied events.
+struct ProfileHook {
+  int which = -1;
+  hipEvent_t* events = nullptr;
+  int n_events = 0;
+  int used = 0;     // pairs recorded
+};
+thread_local ProfileHook g_hook;
+
+struct ProfileScope {
+  bool on;
+  hipStream_t st;
+  ProfileScope(int which, hipStream_t s) : on(false), st(s) {
+    if (g_hook.which == which && g_hook.events && 2 * g_hook.used + 1 < g_hook.n_events) {
+      on = true;
+      (void)hipEventRecord(g_hook.events[2 * g_hook.used], st);
+    }
+  }
+  ~ProfileScope() {
+    if (on) {
+      (void)hipEventRecord(g_hook.events[2 * g_hook.used + 1], st);
+      ++g_hook.used;
+    }
+  }
+};
+
 #define KD_TRY(expr)                           \
   do {                                         \
     if ((expr) != hipSuccess) return KD_ERR_LAUNCH; \
   } while (0)
 
 kd_status run_forward(const Problem& q, hipStream_t st) {
-  KD_TRY(kd::launch_stats(q, st));
+  {
+    ProfileScope ps(KD_PROF_STATS, st);
+    KD_TRY(kd::launch_stats(q, st));
+  }
   KD_TRY(kd::launch_combine(q, st));
   if (q.kind == KD_JSD) {
-    KD_TRY(kd::launch_jsd_rows(q, st));
+    {
+      ProfileScope ps(KD_PROF_JSD_ROWS, st);
+      KD_TRY(kd::launch_jsd_rows(q, st));
+    }
     KD_TRY(kd::launch_combine_jsd(q, st));
   }
   KD_TRY(kd::launch_finalize(q, st));
@@ -200,7 +232,10 @@ kd_status kd_loss_fwd_bwd(const kd_loss_params* params, const void* h_t, const v
   bool first = true;
   for (int64_t v0 = 0; v0 < q.V; v0 += q.V_c) {
     const int width = (int)((q.V - v0 < q.V_c) ? q.V - v0 : q.V_c);
-    KD_TRY(kd::launch_grad_chunk(q, (int)v0, width, st));
+    {
+      ProfileScope ps(KD_PROF_GRAD, st);
+      KD_TRY(kd::launch_grad_chunk(q, (int)v0, width, st));
+    }
     // W_s[chunk]^T [H_s][V_c]: the K-contiguous operand of grad_h_s
     KD_TRY(kd::launch_transpose(static_cast<const char*>(q.W_s) + (size_t)v0 * q.H_s * 2, q.H_s, width, q.H_s,
                                 q.W_sT, q.V_c, (int)round_up(width, 64), st));
@@ -211,19 +246,41 @@ kd_status kd_loss_fwd_bwd(const kd_loss_params* params, const void* h_t, const v
     gw.out = static_cast<char*>(q.grad_W_s) + (size_t)v0 * q.H_s * gsz;
     gw.ldo = q.H_s; gw.out_split_stride = 0;
     gw.out_f32 = q.grad_f32; gw.accumulate = q.accumulate_grad_W;
-    KD_TRY(kd::launch_gemm(gw, q.n_cu, st));
+    {
+      ProfileScope ps(KD_PROF_GEMM_GRAD_W, st);
+      KD_TRY(kd::launch_gemm(gw, q.n_cu, st));
+    }
     kd::GemmDesc gh{};   // grad_h_s[t][h] += sum_v W_sT[h][v] dz[t][v]
     gh.A = q.W_sT; gh.lda = q.V_c; gh.M = q.H_s;
     gh.B = q.dz; gh.ldb = q.V_c; gh.N = q.T;
     gh.K = (int)round_up(width, 64); gh.ksteps_per_split = q.ksteps_h;
     gh.out = q.gh32; gh.ldo = q.H_s; gh.out_split_stride = (int64_t)q.T * q.H_s;
     gh.out_f32 = 1; gh.accumulate = first ? 0 : 1;
-    KD_TRY(kd::launch_gemm(gh, q.n_cu, st));
+    {
+      ProfileScope ps(KD_PROF_GEMM_GRAD_H, st);
+      KD_TRY(kd::launch_gemm(gh, q.n_cu, st));
+    }
     first = false;
   }
   KD_TRY(kd::launch_gradh_finish(q, st));
   return KD_OK;
 }
+
+kd_status kd_loss_profile_hook(int which, void** events, int n_events) {
+  if (which < 0) {
+    g_hook = ProfileHook{};
+    return KD_OK;
+  }
+  if (which > KD_PROF_GEMM_GRAD_H) return KD_ERR_PARAM;
+  if (!events || n_events < 2) return KD_ERR_NULL;
+  g_hook.which = which;
+  g_hook.events = reinterpret_cast<hipEvent_t*>(events);
+  g_hook.n_events = n_events;
+  g_hook.used = 0;
+  return KD_OK;
+}
+
+int kd_loss_profile_count(void) { return g_hook.used; }
 
 const char* kd_status_string(kd_status status) {
   switch (status) {

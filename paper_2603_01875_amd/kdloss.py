@@ -55,6 +55,10 @@ def lib():
         L.kd_loss_fwd_bwd.restype = ctypes.c_int
         L.kd_loss_fwd.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.kd_loss_fwd.restype = ctypes.c_int
+        L.kd_loss_profile_hook.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_void_p), ctypes.c_int]
+        L.kd_loss_profile_hook.restype = ctypes.c_int
+        L.kd_loss_profile_count.argtypes = []
+        L.kd_loss_profile_count.restype = ctypes.c_int
         L.kd_status_string.argtypes = [ctypes.c_int]
         L.kd_status_string.restype = ctypes.c_char_p
         _lib = L
@@ -83,6 +87,39 @@ def kd_loss_plan_info(params: KdLossParams):
     if st != KD_OK:
         raise KdLossError(st)
     return int(vc.value), int(nl.value)
+
+
+PROF_STATS, PROF_JSD_ROWS, PROF_GRAD, PROF_GEMM_GRAD_W, PROF_GEMM_GRAD_H = range(5)
+
+
+class KernelTimer:
+    """Brackets every launch of one kernel family with HIP events (kd_loss_profile_hook).
+
+    with KernelTimer(PROF_STATS, max_launches) as kt: ...calls...; then kt.durations_ms()
+    after a device synchronisation.
+    """
+
+    def __init__(self, which, max_launches):
+        import torch
+        self.which = which
+        self.events = [torch.cuda.Event(enable_timing=True) for _ in range(2 * max_launches)]
+        for e in self.events:
+            e.record()                      # materialise the underlying hipEvent_t
+        self.arr = (ctypes.c_void_p * len(self.events))(*[e.cuda_event for e in self.events])
+        self.count = 0
+
+    def __enter__(self):
+        st = lib().kd_loss_profile_hook(self.which, self.arr, len(self.events))
+        if st != KD_OK:
+            raise KdLossError(st)
+        return self
+
+    def __exit__(self, *exc):
+        self.count = lib().kd_loss_profile_count()
+        lib().kd_loss_profile_hook(-1, None, 0)
+
+    def durations_ms(self):
+        return [self.events[2 * i].elapsed_time(self.events[2 * i + 1]) for i in range(self.count)]
 
 
 def _ptr(t):
