@@ -103,9 +103,10 @@ __device__ __forceinline__ int acc_n(int wn, int nt, int lane) {
 // are already in flight while the epilogue of the current one runs.
 //
 // Synchronisation: each thread issues exactly LOADS_PER_STEP direct loads per
-// k-step and vector-memory loads complete in order, so "at most LOADS_PER_STEP
-// operations outstanding" implies that everything older than the youngest
-// k-step has landed.  Other vector-memory traffic of the thread (epilogue
+// k-step (the last three k-steps of a workgroup re-issue the final loads as
+// dummies so that this holds to the end) and vector-memory loads complete in
+// order, so "at most LOADS_PER_STEP operations outstanding" implies that
+// everything older than the youngest k-step has landed.  Other vector-memory traffic of the thread (epilogue
 // loads and stores) only adds to the counter, which makes the wait stricter,
 // never weaker.
 constexpr int LOADS_PER_STEP = A_LOADS + B_LOADS;
@@ -113,13 +114,16 @@ static_assert(LOADS_PER_STEP == 12, "s_waitcnt immediates below assume 12 loads 
 
 typedef __attribute__((address_space(3))) void lds_void_t;
 
+// sched_group_barrier masks
+constexpr int SG_MFMA = 0x008, SG_VMEM = 0x010, SG_DSREAD = 0x100;
+
 template <int NPHASE, class Work, class Epi>
 __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
                                           const int lda0, const int lda1, const int ldb0, const int ldb1,
                                           char* smem) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = uniform(tid >> 6);
   const int wm = wave & 1, wn = wave >> 1;
 
   const int n_items = work.n_items();
@@ -131,39 +135,45 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
   // global memory is the logical one that the XOR layout keeps in that slot.
   const int lrow = tid >> 3;
   const int lchunk = (tid & 7) ^ ((tid >> 4) & 7);
-  int l_item = 0, l_phase = 0, l_k = 0;
+  int l_item = 0, l_phase = 0, l_k = 0, l_nk;
   bool more = true;
   WorkItem li = work.item(0);
-  uint32_t aoff[A_LOADS], boff[B_LOADS];
-  auto set_offsets = [&]() {
+  const char *l_pa, *l_pb;                  // uniform: tile base + k offset, in bytes
+  uint32_t aoff[A_LOADS], boff[B_LOADS];    // per lane: byte offset of its 16 bytes inside the k-slab
+  auto set_cursor = [&]() {
+    const uint32_t la = (uint32_t)(l_phase ? lda1 : lda0), lb = (uint32_t)(l_phase ? ldb1 : ldb0);
 #pragma unroll
     for (int j = 0; j < A_LOADS; ++j) {
       int r = lrow + 32 * j;
       r = r < li.a_rows ? r : li.a_rows - 1;
-      aoff[j] = (uint32_t)r * (uint32_t)(l_phase ? lda1 : lda0) + lchunk * 8;
+      aoff[j] = ((uint32_t)r * la + lchunk * 8) * 2;
     }
 #pragma unroll
     for (int j = 0; j < B_LOADS; ++j) {
       int r = lrow + 32 * j;
       r = r < li.b_rows ? r : li.b_rows - 1;
-      boff[j] = (uint32_t)r * (uint32_t)(l_phase ? ldb1 : ldb0) + lchunk * 8;
+      boff[j] = ((uint32_t)r * lb + lchunk * 8) * 2;
     }
+    l_pa = (const char*)uniform(l_phase ? li.A1 : li.A0);
+    l_pb = (const char*)uniform(l_phase ? li.B1 : li.B0);
+    l_nk = l_phase ? li.nk1 : li.nk0;
   };
-  set_offsets();
+  set_cursor();
 
   auto issue_loads = [&](int stage) {
-    const bf16_t* pa = uniform((l_phase ? li.A1 : li.A0) + l_k * BK);
-    const bf16_t* pb = uniform((l_phase ? li.B1 : li.B0) + l_k * BK);
     char* sbase = smem + stage * STAGE_BYTES + wave * 1024;
 #pragma unroll
     for (int j = 0; j < A_LOADS; ++j)
-      __builtin_amdgcn_global_load_lds((const void*)(pa + aoff[j]), (lds_void_t*)(sbase + j * 4096), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const void*)(l_pa + aoff[j]), (lds_void_t*)(sbase + j * 4096), 16, 0, 0);
 #pragma unroll
     for (int j = 0; j < B_LOADS; ++j)
-      __builtin_amdgcn_global_load_lds((const void*)(pb + boff[j]),
+      __builtin_amdgcn_global_load_lds((const void*)(l_pb + boff[j]),
                                        (lds_void_t*)(sbase + A_STAGE_BYTES + j * 4096), 16, 0, 0);
-    // advance
-    if (++l_k == (l_phase ? li.nk1 : li.nk0)) {
+  };
+  auto advance = [&]() {
+    l_pa += BK * 2;
+    l_pb += BK * 2;
+    if (++l_k == l_nk) {
       l_k = 0;
       if (NPHASE > 1 && l_phase == 0) {
         l_phase = 1;
@@ -173,7 +183,17 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
         if (l_item < n_items) li = work.item(l_item);
         else more = false;
       }
-      if (more) set_offsets();
+      if (more) {
+        set_cursor();
+      } else {
+        // past the end: keep re-reading the last k-step (valid memory, data unused) so that
+        // every k-step of the loop issues the same number of loads
+        l_item = n_items - 1;
+        l_phase = NPHASE - 1;
+        l_k = l_nk - 1;
+        l_pa -= BK * 2;
+        l_pb -= BK * 2;
+      }
     }
   };
 
@@ -192,18 +212,7 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
   if (NPHASE > 1) zero_acc(acc1);
 
   int stage = 0;       // LDS stage of the k-step being consumed
-  int ahead = 0;       // k-steps issued and not yet released
 
-  // Wait until the operands of the next k-step to consume have landed (this wave's share),
-  // then meet the other waves: after the barrier every wave's share has landed and nobody
-  // reads the stage consumed before any more.
-  auto sync_next = [&]() {
-    if (ahead < 3) {
-      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    } else {
-      asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    }
-  };
   auto read_frags = [&](int st, int ks, bf16x8 (&af)[MI], bf16x8 (&bfr)[NI]) {
     const char* base = smem + st * STAGE_BYTES;
 #pragma unroll
@@ -223,56 +232,63 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
   bf16x8 fa0[MI], fb0[NI];
 
   // One k-step.  On entry fa0/fb0 hold sub-step 0.  The barrier sits before the last group
-  // of MFMAs so that the first fragments of the next k-step are read in their shadow.
-  auto kstep = [&](AccTile& acc, bool last) {
+  // of MFMAs: after it the stage just read is refilled with the k-step three ahead and the
+  // first fragments of the next k-step are read, all in the shadow of that last group.
+  auto kstep = [&](AccTile& acc) {
     bf16x8 fa1[MI], fb1[NI];
+    const int next = stage == 2 ? 0 : stage + 1;
     read_frags(stage, 1, fa1, fb1);
     mma(acc, fa0, fb0);
+    __builtin_amdgcn_sched_barrier(0);
     read_frags(stage, 2, fa0, fb0);
     mma(acc, fa1, fb1);
+    __builtin_amdgcn_sched_barrier(0);
     read_frags(stage, 3, fa1, fb1);
     mma(acc, fa0, fb0);
-    const int next = stage == 2 ? 0 : stage + 1;
-    if (!last) {
-      sync_next();                      // stage `stage` is free, stage `next` is ready
-      if (more) {
-        issue_loads(stage);
-        ++ahead;
-      }
-      read_frags(next, 0, fa0, fb0);
-    }
+    __builtin_amdgcn_sched_barrier(0);
+    // k-steps g, g+1, g+2 are in flight; at most the 12 loads of g+2 may still be pending
+    asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    issue_loads(stage);
+    read_frags(next, 0, fa0, fb0);
     mma(acc, fa1, fb1);
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+      __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(SG_DSREAD, 2, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(SG_VMEM, 3, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    advance();
     stage = next;
-    --ahead;
   };
 
   // ---- prologue: three k-steps in flight, first fragments read ------------------------------
   issue_loads(0);
-  ++ahead;
-  if (more) { issue_loads(1); ++ahead; }
-  if (more) { issue_loads(2); ++ahead; }
-  if (ahead > 1) {
-    if (ahead > 2) asm volatile("s_waitcnt vmcnt(24)\n\ts_barrier" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(12)\n\ts_barrier" ::: "memory");
-  } else {
-    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-  }
+  advance();
+  issue_loads(1);
+  advance();
+  issue_loads(2);
+  advance();
+  asm volatile("s_waitcnt vmcnt(24)\n\ts_barrier" ::: "memory");
   read_frags(0, 0, fa0, fb0);
 
   for (int c_item = 0; c_item < n_items; ++c_item) {
     const WorkItem ci = work.item(c_item);
     epi.begin_item(ci);
-    const bool last_item = c_item + 1 == n_items;
-    if (NPHASE > 1) {
-      for (int k = 0; k < ci.nk0; ++k) kstep(acc0, false);
-      for (int k = 0; k < ci.nk1; ++k) kstep(acc1, last_item && k + 1 == ci.nk1);
-    } else {
-      for (int k = 0; k < ci.nk0; ++k) kstep(acc0, last_item && k + 1 == ci.nk0);
-    }
+    for (int k = 0; k < ci.nk0; ++k) kstep(acc0);
+    if (NPHASE > 1)
+      for (int k = 0; k < ci.nk1; ++k) kstep(acc1);
     epi.end_item(ci, acc0, acc1);
     zero_acc(acc0);
     if (NPHASE > 1) zero_acc(acc1);
   }
+  // the loads issued past the end still target this workgroup's LDS: let them land
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
 }  // namespace kd
