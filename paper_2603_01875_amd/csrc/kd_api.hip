@@ -64,7 +64,7 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward) {
   q.V_c = (int)vc;
 
   // split-K of the grad_h_s product so that a chunk offers about one tile per CU
-  const int tiles_h = ((q.H_s + kd::kTileM - 1) / kd::kTileM) * q.n_tt;
+  const int tiles_h = ((q.H_s + kd::kGemmTileM - 1) / kd::kGemmTileM) * q.n_tt;
   int sk = q.n_cu / tiles_h;
   if (sk < 1) sk = 1;
   if (sk > 8) sk = 8;
@@ -242,7 +242,7 @@ kd_status kd_loss_fwd_bwd(const kd_loss_params* params, const void* h_t, const v
     kd::GemmDesc gw{};   // grad_W_s[v][h] = sum_t h_sT[h][t] dzT[v][t]
     gw.A = q.h_sT; gw.lda = q.T_pad; gw.M = q.H_s;
     gw.B = q.dzT; gw.ldb = q.T_pad; gw.N = width;
-    gw.K = q.T_pad; gw.ksteps_per_split = 0;
+    gw.K = q.T_pad; gw.k_per_split = 0;
     gw.out = static_cast<char*>(q.grad_W_s) + (size_t)v0 * q.H_s * gsz;
     gw.ldo = q.H_s; gw.out_split_stride = 0;
     gw.out_f32 = q.grad_f32; gw.accumulate = q.accumulate_grad_W;
@@ -253,7 +253,7 @@ kd_status kd_loss_fwd_bwd(const kd_loss_params* params, const void* h_t, const v
     kd::GemmDesc gh{};   // grad_h_s[t][h] += sum_v W_sT[h][v] dz[t][v]
     gh.A = q.W_sT; gh.lda = q.V_c; gh.M = q.H_s;
     gh.B = q.dz; gh.ldb = q.V_c; gh.N = q.T;
-    gh.K = (int)round_up(width, 64); gh.ksteps_per_split = q.ksteps_h;
+    gh.K = (int)round_up(width, 64); gh.k_per_split = q.ksteps_h * 64;
     gh.out = q.gh32; gh.ldo = q.H_s; gh.out_split_stride = (int64_t)q.T * q.H_s;
     gh.out_f32 = 1; gh.accumulate = first ? 0 : 1;
     {

@@ -13,7 +13,22 @@
 #include "kd_mfma.hpp"
 #include "kd_launch.h"
 
+#ifndef KD_GEMM_MI
+#define KD_GEMM_MI 4
+#define KD_GEMM_BK 32
+#define KD_GEMM_NST 4
+#endif
+
 namespace kd {
+
+typedef TileCfg<2, 64, 3> LCfg;   // logit tiles: two accumulators of 128 x 256, three LDS stages
+typedef TileCfg<KD_GEMM_MI, KD_GEMM_BK, KD_GEMM_NST> GCfg;   // backward products: one accumulator
+constexpr int BK = LCfg::BK;
+constexpr int BM = LCfg::BM;
+constexpr int MI = LCfg::MI;
+typedef LCfg::Acc AccTile;
+__device__ __forceinline__ int acc_m(int wm, int mt, int r, int lane) { return LCfg::acc_m(wm, mt, r, lane); }
+__device__ __forceinline__ int acc_n(int wn, int nt, int lane) { return LCfg::acc_n(wn, nt, lane); }
 
 // ------------------------------------------------------------------------------------------
 // work maps
@@ -309,7 +324,7 @@ KD_KERNEL void stats_kernel(const LogitArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   SplitWork work(a);
   StatsEpi<KIND> epi(a.c);
-  tile_loop<2>(work, epi, a.H_s, a.H_t, a.H_s, a.H_t, smem);
+  tile_loop<2, LCfg>(work, epi, a.H_s, a.H_t, a.H_s, a.H_t, smem);
   epi.write(a, work.tt, work.split);
 }
 
@@ -317,7 +332,7 @@ KD_KERNEL void jsd_rows_kernel(const LogitArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   SplitWork work(a);
   JsdEpi epi(a, work.tt);
-  tile_loop<2>(work, epi, a.H_s, a.H_t, a.H_s, a.H_t, smem);
+  tile_loop<2, LCfg>(work, epi, a.H_s, a.H_t, a.H_s, a.H_t, smem);
   epi.write(a, work.tt, work.split);
 }
 
@@ -326,7 +341,7 @@ KD_KERNEL void grad_kernel(const LogitArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   ChunkWork work(a);
   GradEpi<KIND> epi(a);
-  tile_loop<2>(work, epi, a.H_s, a.H_t, a.H_s, a.H_t, smem);
+  tile_loop<2, LCfg>(work, epi, a.H_s, a.H_t, a.H_s, a.H_t, smem);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -336,9 +351,9 @@ struct GemmArgs {
   const bf16_t* A; const bf16_t* B;
   int lda, ldb;
   int M, N;            // valid rows of A / of B
-  int K;               // contraction length, a multiple of BK
+  int K;               // contraction length, a multiple of 64
   int n_ksplit;        // split-K parts; part s writes out + s * out_split_stride
-  int ksteps;          // k-steps of BK per part
+  int ksteps;          // k-steps per part
   void* out; int64_t ldo; int64_t out_split_stride;   // in elements
   int out_f32;         // 1: float, 0: bf16
   int accumulate;      // 1: out += D
@@ -358,14 +373,14 @@ struct GemmWork {
     const int q = i * G + L;
     const int mt = q % a.n_mt, rest = q / a.n_mt;
     const int nt = rest % a.n_nt, ks = rest / a.n_nt;
-    const int k0 = ks * a.ksteps * BK;
+    const int k0 = ks * a.ksteps * GCfg::BK;
     WorkItem it;
-    it.A0 = it.A1 = a.A + (int64_t)mt * BM * a.lda + k0;
+    it.A0 = it.A1 = a.A + (int64_t)mt * GCfg::BM * a.lda + k0;
     it.B0 = it.B1 = a.B + (int64_t)nt * BN * a.ldb + k0;
-    it.a_rows = min(BM, a.M - mt * BM);
+    it.a_rows = min(GCfg::BM, a.M - mt * GCfg::BM);
     it.b_rows = min(BN, a.N - nt * BN);
-    it.nk0 = it.nk1 = min(a.ksteps, a.K / BK - ks * a.ksteps);
-    it.m0 = mt * BM;
+    it.nk0 = it.nk1 = min(a.ksteps, a.K / GCfg::BK - ks * a.ksteps);
+    it.m0 = mt * GCfg::BM;
     it.n0 = nt * BN;
     it.aux = ks;
     return it;
@@ -381,17 +396,17 @@ struct StoreEpi {
     wn = threadIdx.x >> 7;
   }
   __device__ void begin_item(const WorkItem&) {}
-  __device__ void end_item(const WorkItem& it, AccTile& acc, AccTile&) {
+  __device__ void end_item(const WorkItem& it, GCfg::Acc& acc, GCfg::Acc&) {
 #pragma unroll
     for (int nt = 0; nt < NI; ++nt) {
-      const int nl = acc_n(wn, nt, lane);
+      const int nl = GCfg::acc_n(wn, nt, lane);
       if (nl >= it.b_rows) continue;
       const int64_t row = (int64_t)(it.n0 + nl) * a.ldo + (int64_t)it.aux * a.out_split_stride;
 #pragma unroll
-      for (int mt = 0; mt < MI; ++mt)
+      for (int mt = 0; mt < GCfg::MI; ++mt)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const int ml = acc_m(wm, mt, 4 * q, lane);
+          const int ml = GCfg::acc_m(wm, mt, 4 * q, lane);
           if (ml >= it.a_rows) continue;
           f32x4 v = {acc[mt][nt][4 * q], acc[mt][nt][4 * q + 1], acc[mt][nt][4 * q + 2], acc[mt][nt][4 * q + 3]};
           if (a.out_f32) {
@@ -419,7 +434,7 @@ KD_KERNEL void gemm_kernel(const GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   GemmWork work(a);
   StoreEpi epi(a);
-  tile_loop<1>(work, epi, a.lda, a.lda, a.ldb, a.ldb, smem);
+  tile_loop<1, GCfg>(work, epi, a.lda, a.lda, a.ldb, a.ldb, smem);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -548,12 +563,11 @@ static int largest_divisor_le(int n, int cap) {
 }
 
 template <class Kern>
-static hipError_t launch_big(Kern kern, int grid, hipStream_t st, const void* args_ptr, size_t args_size) {
-  (void)args_size;
-  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
+static hipError_t launch_big(Kern kern, int grid, int smem_bytes, hipStream_t st, const void* args_ptr) {
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes);
   if (e != hipSuccess) return e;
   void* params[] = {const_cast<void*>(args_ptr)};
-  return hipLaunchKernel((const void*)kern, dim3(grid), dim3(NTHREADS), params, SMEM_BYTES, st);
+  return hipLaunchKernel((const void*)kern, dim3(grid), dim3(NTHREADS), params, smem_bytes, st);
 }
 
 static LogitArgs make_logit_args(const Problem& p) {
@@ -577,9 +591,9 @@ hipError_t launch_stats(const Problem& p, hipStream_t st) {
   a.partials = p.partials;
   const int grid = p.n_tt * p.n_split;
   switch (p.kind) {
-    case 0: return launch_big(stats_kernel<0>, grid, st, &a, sizeof(a));
-    case 1: return launch_big(stats_kernel<1>, grid, st, &a, sizeof(a));
-    default: return launch_big(stats_kernel<2>, grid, st, &a, sizeof(a));
+    case 0: return launch_big(stats_kernel<0>, grid, LCfg::SMEM_BYTES, st, &a);
+    case 1: return launch_big(stats_kernel<1>, grid, LCfg::SMEM_BYTES, st, &a);
+    default: return launch_big(stats_kernel<2>, grid, LCfg::SMEM_BYTES, st, &a);
   }
 }
 
@@ -589,7 +603,7 @@ hipError_t launch_jsd_rows(const Problem& p, hipStream_t st) {
   a.ba = largest_divisor_le(p.n_tt, 4);
   a.bb = largest_divisor_le(p.n_split, 8);
   a.partials = p.partials;
-  return launch_big(jsd_rows_kernel, p.n_tt * p.n_split, st, &a, sizeof(a));
+  return launch_big(jsd_rows_kernel, p.n_tt * p.n_split, LCfg::SMEM_BYTES, st, &a);
 }
 
 hipError_t launch_combine(const Problem& p, hipStream_t st) {
@@ -622,9 +636,9 @@ hipError_t launch_grad_chunk(const Problem& p, int v0, int width, hipStream_t st
   const int tiles = p.n_tt * a.n_vt;
   int grid = tiles < p.n_cu ? tiles : p.n_cu;
   switch (p.kind) {
-    case 0: return launch_big(grad_kernel<0>, grid, st, &a, sizeof(a));
-    case 1: return launch_big(grad_kernel<1>, grid, st, &a, sizeof(a));
-    default: return launch_big(grad_kernel<2>, grid, st, &a, sizeof(a));
+    case 0: return launch_big(grad_kernel<0>, grid, LCfg::SMEM_BYTES, st, &a);
+    case 1: return launch_big(grad_kernel<1>, grid, LCfg::SMEM_BYTES, st, &a);
+    default: return launch_big(grad_kernel<2>, grid, LCfg::SMEM_BYTES, st, &a);
   }
 }
 
@@ -640,16 +654,16 @@ hipError_t launch_gemm(const GemmDesc& d, int n_cu, hipStream_t st) {
   GemmArgs a{};
   a.A = (const bf16_t*)d.A; a.B = (const bf16_t*)d.B;
   a.lda = d.lda; a.ldb = d.ldb; a.M = d.M; a.N = d.N; a.K = d.K;
-  const int ksteps_total = d.K / BK;
-  a.ksteps = d.ksteps_per_split > 0 ? d.ksteps_per_split : ksteps_total;
+  const int ksteps_total = d.K / GCfg::BK;
+  a.ksteps = d.k_per_split > 0 ? d.k_per_split / GCfg::BK : ksteps_total;
   a.n_ksplit = (ksteps_total + a.ksteps - 1) / a.ksteps;     // every part has at least one k-step
   a.out = d.out; a.ldo = d.ldo; a.out_split_stride = d.out_split_stride;
   a.out_f32 = d.out_f32; a.accumulate = d.accumulate;
-  a.n_mt = (d.M + BM - 1) / BM;
+  a.n_mt = (d.M + GCfg::BM - 1) / GCfg::BM;
   a.n_nt = (d.N + BN - 1) / BN;
   const int tiles = a.n_mt * a.n_nt * a.n_ksplit;
   const int grid = tiles < n_cu ? tiles : n_cu;
-  return launch_big(gemm_kernel, grid, st, &a, sizeof(a));
+  return launch_big(gemm_kernel, grid, GCfg::SMEM_BYTES, st, &a);
 }
 
 hipError_t launch_gradh_finish(const Problem& p, hipStream_t st) {

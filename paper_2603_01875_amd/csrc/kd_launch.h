@@ -9,6 +9,7 @@ namespace kd {
 constexpr int kNumCU = 256;            // MI355X: 8 XCDs x 32 CUs; persistent grids are sized for it
 constexpr int kTileM = 128;            // vocabulary rows per logit tile
 constexpr int kTileN = 256;            // token rows per logit tile
+constexpr int kGemmTileM = 256;        // rows of the first operand per tile of the backward products
 
 // Everything a launch needs, resolved by the planner in kd_api.hip.
 struct Problem {
@@ -40,7 +41,8 @@ struct GemmDesc {
   const void *A, *B;
   int lda, ldb, M, N;
   int K;                  // multiple of 64
-  int ksteps_per_split;   // split-K: k-steps of 64 per part (0 = no split); part s writes out + s * out_split_stride
+  int k_per_split;        // split-K: elements per part, a multiple of 64 (0 = no split); part s writes
+                          // out + s * out_split_stride
   void* out;
   int64_t ldo, out_split_stride;
   int out_f32, accumulate;

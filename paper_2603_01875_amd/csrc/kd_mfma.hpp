@@ -24,23 +24,65 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 
-constexpr int BM = 128;          // tile rows of A (MFMA M axis)
-constexpr int BN = 256;          // tile rows of B (MFMA N axis)
-constexpr int BK = 64;           // k-step, in elements (128 bytes per tile row)
-constexpr int NTHREADS = 256;
-constexpr int MI = 2;            // 32-row MFMA blocks per wave along M
+constexpr int NTHREADS = 256;    // 4 waves, 2 (M) x 2 (N)
 constexpr int NI = 4;            // 32-row MFMA blocks per wave along N
-constexpr int A_LOADS = BM * BK / 8 / NTHREADS;   // 16-byte loads per thread per k-step (4)
-constexpr int B_LOADS = BN * BK / 8 / NTHREADS;   // (8)
-constexpr int A_STAGE_BYTES = BM * BK * 2;
-constexpr int B_STAGE_BYTES = BN * BK * 2;
-constexpr int STAGE_BYTES = A_STAGE_BYTES + B_STAGE_BYTES;
-constexpr int NSTAGE = 3;
-constexpr int SMEM_BYTES = NSTAGE * STAGE_BYTES;   // 144 KiB of the 160 KiB LDS
+constexpr int BN = 256;          // tile rows of B (MFMA N axis): 2 waves x NI x 32
 
-typedef f32x16 AccTile[MI][NI];
+// Tile shape and pipeline depth.  MI 32-row MFMA blocks per wave along M give a tile of
+// BM = 64 MI rows of A; a k-step covers BK elements (32 or 64); NST LDS stages of one
+// k-step each.
+//
+// LDS tile layout: row r occupies ROWB = 2 BK bytes; its CH = BK/8 16-byte chunks are
+// permuted by XOR with a few row bits so that 16 lanes reading the same logical chunk of
+// 16 consecutive rows hit 16 distinct 16-byte bank groups (conflict-free ds_read_b128),
+// while the direct loads still write each wave's 1 KiB linearly.
+template <int MI_, int BK_, int NST_>
+struct TileCfg {
+  static constexpr int MI = MI_;
+  static constexpr int BK = BK_;
+  static constexpr int NST = NST_;
+  static constexpr int KS = BK_ / 16;                      // MFMA sub-steps per k-step
+  static constexpr int BM = 64 * MI_;
+  static constexpr int ROWB = BK_ * 2;
+  static constexpr int CH = BK_ / 8;
+  static constexpr int SW_SHIFT = BK_ == 64 ? 1 : 2;       // swizzle = (row >> SW_SHIFT) & (CH - 1)
+  static constexpr int ROWS_PER_LOAD = NTHREADS / CH;      // tile rows covered by one load instruction
+  static constexpr int A_LOADS = BM / ROWS_PER_LOAD;       // 16-byte loads per thread per k-step
+  static constexpr int B_LOADS = BN / ROWS_PER_LOAD;
+  static constexpr int LOADS = A_LOADS + B_LOADS;
+  static constexpr int LOADS_PER_SUB = (LOADS + KS - 1) / KS;
+  static constexpr int LOADS_BEFORE_BARRIER = (KS - 1) * LOADS_PER_SUB < LOADS ? (KS - 1) * LOADS_PER_SUB : LOADS;
+  static constexpr int A_STAGE_BYTES = BM * ROWB;
+  static constexpr int B_STAGE_BYTES = BN * ROWB;
+  static constexpr int STAGE_BYTES = A_STAGE_BYTES + B_STAGE_BYTES;
+  static constexpr int SMEM_BYTES = NST_ * STAGE_BYTES;
+  // vector-memory operations that may still be pending when k-step g+1 has to be in LDS:
+  // whole k-steps g+2 .. g+NST-2 and the part of k-step g+NST-1 issued before the barrier
+  static constexpr int WAIT_STEADY = (NST_ - 3) * LOADS + LOADS_BEFORE_BARRIER;
+  static constexpr int WAIT_PROLOGUE = (NST_ - 2) * LOADS;
+  static_assert(BK_ == 32 || BK_ == 64, "k-step");
+  static_assert(NST_ >= 3, "the stage being refilled is the one released one k-step earlier");
+  static_assert(SMEM_BYTES <= 160 * 1024, "LDS of a gfx950 CU");
+  static_assert(WAIT_STEADY < 64 && WAIT_PROLOGUE < 64, "vmcnt is a 6-bit counter");
+  typedef f32x16 Acc[MI_][NI];
+  // Coordinates of accumulator element (mt, nt, r) of this lane inside the tile.
+  static __device__ __forceinline__ int acc_m(int wm, int mt, int r, int lane) {
+    return wm * (32 * MI_) + mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+  }
+  static __device__ __forceinline__ int acc_n(int wn, int nt, int lane) {
+    return wn * 128 + nt * 32 + (lane & 31);
+  }
+  static __device__ __forceinline__ void zero(Acc& acc) {
+#pragma unroll
+    for (int i = 0; i < MI_; ++i)
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  }
+};
 
-// One unit of work for a persistent workgroup: a 128 x 256 tile whose value is
+// One unit of work for a persistent workgroup: a BM x 256 tile whose value is
 // built in NPHASE accumulators (phase p contracts A[p] with B[p] over K[p]).
 // (Scalar fields, no arrays: the struct must stay in scalar registers.)
 struct WorkItem {
@@ -63,64 +105,43 @@ __device__ __forceinline__ const T* uniform(const T* p) {
   return (const T*)(((uint64_t)hi << 32) | lo);
 }
 
-// LDS tile layout: row r occupies bytes [128 r, 128 r + 128); its eight 16-byte
-// chunks are permuted by XOR with ((r >> 1) & 7) so that 16 lanes reading the
-// same chunk index of 16 consecutive rows hit 16 distinct 16-byte bank groups.
-__device__ __forceinline__ int lds_off(int row, int chunk) {
-  return row * (BK * 2) + ((chunk ^ ((row >> 1) & 7)) << 4);
-}
-
-__device__ __forceinline__ void zero_acc(AccTile& acc) {
-#pragma unroll
-  for (int i = 0; i < MI; ++i)
-#pragma unroll
-    for (int j = 0; j < NI; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-}
-
-// Coordinates of accumulator element (mt, nt, r) of this lane inside the tile.
-__device__ __forceinline__ int acc_m(int wm, int mt, int r, int lane) {
-  return wm * 64 + mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-}
-__device__ __forceinline__ int acc_n(int wn, int nt, int lane) {
-  return wn * 128 + nt * 32 + (lane & 31);
-}
-
 // Persistent tile loop with a continuous software pipeline.
 //
 // Work:  int n_items() const;  WorkItem item(int i) const;   (wave-uniform)
 // Epi:   void begin_item(const WorkItem&)            called before the first k-step of an item
-//        void end_item(const WorkItem&, AccTile& acc0, AccTile& acc1)
+//        void end_item(const WorkItem&, Acc& acc0, Acc& acc1)
 //                                                    called after the last k-step of an item
 // ld*[p] are the same for every item of a launch; the k-step counts may differ per item.
 //
-// Pipeline: three LDS stages filled by direct global->LDS loads (16 bytes per
-// lane, no staging registers).  The loads of k-step g+3 are issued near the
-// end of k-step g, into the stage it has just finished reading; one barrier
-// per k-step.  The stream of k-steps does
-// not drain between phases or between items, so the operands of the next tile
-// are already in flight while the epilogue of the current one runs.
+// Pipeline: NST LDS stages filled by direct global->LDS loads (16 bytes per lane, no
+// staging registers).  While k-step g is multiplied, the loads of k-step g+NST-1 are
+// issued a few at a time between its MFMAs (a wave issues in order, so a burst of loads
+// would starve the matrix pipe), into the stage that k-step g-1 released.  One barrier per
+// k-step, placed before the last group of MFMAs so that the first fragments of k-step g+1
+// are read in their shadow.  The stream of k-steps does not drain between phases or
+// between items: the operands of the next tile are in flight while the epilogue runs.
 //
-// Synchronisation: each thread issues exactly LOADS_PER_STEP direct loads per
-// k-step (the last three k-steps of a workgroup re-issue the final loads as
-// dummies so that this holds to the end) and vector-memory loads complete in
-// order, so "at most LOADS_PER_STEP operations outstanding" implies that
-// everything older than the youngest k-step has landed.  Other vector-memory traffic of the thread (epilogue
-// loads and stores) only adds to the counter, which makes the wait stricter,
-// never weaker.
-constexpr int LOADS_PER_STEP = A_LOADS + B_LOADS;
-static_assert(LOADS_PER_STEP == 12, "s_waitcnt immediates below assume 12 loads per k-step");
-
+// Synchronisation: every k-step issues exactly LOADS direct loads per thread (past the end
+// of its work a workgroup re-issues its last loads as dummies so that this holds to the
+// end) and vector-memory loads complete in order, so "at most WAIT_STEADY operations
+// outstanding" implies that k-step g+1 has landed.  Other vector-memory traffic of the
+// thread (epilogue loads and stores) only adds to the counter, which makes the wait
+// stricter, never weaker.
 typedef __attribute__((address_space(3))) void lds_void_t;
 
 // sched_group_barrier masks
 constexpr int SG_MFMA = 0x008, SG_VMEM = 0x010, SG_DSREAD = 0x100;
 
-template <int NPHASE, class Work, class Epi>
+template <int NPHASE, class Cfg, class Work, class Epi>
 __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
                                           const int lda0, const int lda1, const int ldb0, const int ldb1,
                                           char* smem) {
+  constexpr int MI = Cfg::MI, NST = Cfg::NST, BK = Cfg::BK, KS = Cfg::KS, CH = Cfg::CH;
+  constexpr int A_LOADS = Cfg::A_LOADS, LOADS = Cfg::LOADS, LPS = Cfg::LOADS_PER_SUB;
+  constexpr int A_STAGE_BYTES = Cfg::A_STAGE_BYTES, STAGE_BYTES = Cfg::STAGE_BYTES;
+  constexpr int ROWB = Cfg::ROWB;
+  typedef typename Cfg::Acc Acc;
+
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = uniform(tid >> 6);
@@ -130,29 +151,26 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
   if (n_items == 0) return;
 
   // ---- load cursor ------------------------------------------------------------------
-  // Lane (wave w, lane l) of load j fills the 16-byte LDS slot j*256 + w*64 + l of the A
-  // (or B) region: tile row j*32 + tid/8, physical chunk tid%8.  The chunk it fetches from
-  // global memory is the logical one that the XOR layout keeps in that slot.
-  const int lrow = tid >> 3;
-  const int lchunk = (tid & 7) ^ ((tid >> 4) & 7);
+  // Load j of lane (wave w, lane l) fills the 16-byte LDS slot j*256 + w*64 + l of the
+  // stage (A region first, then B): tile row j*ROWS_PER_LOAD + tid/CH, physical chunk
+  // tid%CH.  The chunk it fetches from global memory is the logical one that the XOR
+  // layout keeps in that slot.
+  const int lrow = tid / CH;
+  const int lchunk = (tid % CH) ^ ((lrow >> Cfg::SW_SHIFT) & (CH - 1));
   int l_item = 0, l_phase = 0, l_k = 0, l_nk;
   bool more = true;
   WorkItem li = work.item(0);
-  const char *l_pa, *l_pb;                  // uniform: tile base + k offset, in bytes
-  uint32_t aoff[A_LOADS], boff[B_LOADS];    // per lane: byte offset of its 16 bytes inside the k-slab
+  const char *l_pa, *l_pb;      // uniform: tile base + k offset, in bytes
+  uint32_t loff[LOADS];         // per lane: byte offset of its 16 bytes inside the k-slab
   auto set_cursor = [&]() {
     const uint32_t la = (uint32_t)(l_phase ? lda1 : lda0), lb = (uint32_t)(l_phase ? ldb1 : ldb0);
 #pragma unroll
-    for (int j = 0; j < A_LOADS; ++j) {
-      int r = lrow + 32 * j;
-      r = r < li.a_rows ? r : li.a_rows - 1;
-      aoff[j] = ((uint32_t)r * la + lchunk * 8) * 2;
-    }
-#pragma unroll
-    for (int j = 0; j < B_LOADS; ++j) {
-      int r = lrow + 32 * j;
-      r = r < li.b_rows ? r : li.b_rows - 1;
-      boff[j] = ((uint32_t)r * lb + lchunk * 8) * 2;
+    for (int j = 0; j < LOADS; ++j) {
+      const bool isA = j < A_LOADS;
+      int r = lrow + Cfg::ROWS_PER_LOAD * (isA ? j : j - A_LOADS);
+      const int lim = isA ? li.a_rows : li.b_rows;
+      r = r < lim ? r : lim - 1;
+      loff[j] = ((uint32_t)r * (isA ? la : lb) + lchunk * 8) * 2;
     }
     l_pa = (const char*)uniform(l_phase ? li.A1 : li.A0);
     l_pb = (const char*)uniform(l_phase ? li.B1 : li.B0);
@@ -160,19 +178,17 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
   };
   set_cursor();
 
-  auto issue_loads = [&](int stage) {
+  // loads [j0, j1) of the k-step under the cursor, into LDS stage `stage`
+  auto issue_loads = [&](int stage, int j0, int j1) {
     char* sbase = smem + stage * STAGE_BYTES + wave * 1024;
 #pragma unroll
-    for (int j = 0; j < A_LOADS; ++j)
-      __builtin_amdgcn_global_load_lds((const void*)(l_pa + aoff[j]), (lds_void_t*)(sbase + j * 4096), 16, 0, 0);
-#pragma unroll
-    for (int j = 0; j < B_LOADS; ++j)
-      __builtin_amdgcn_global_load_lds((const void*)(l_pb + boff[j]),
-                                       (lds_void_t*)(sbase + A_STAGE_BYTES + j * 4096), 16, 0, 0);
+    for (int j = j0; j < j1; ++j)
+      __builtin_amdgcn_global_load_lds((const void*)((j < A_LOADS ? l_pa : l_pb) + loff[j]),
+                                       (lds_void_t*)(sbase + j * 4096), 16, 0, 0);
   };
   auto advance = [&]() {
-    l_pa += BK * 2;
-    l_pb += BK * 2;
+    l_pa += ROWB;
+    l_pb += ROWB;
     if (++l_k == l_nk) {
       l_k = 0;
       if (NPHASE > 1 && l_phase == 0) {
@@ -191,90 +207,102 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
         l_item = n_items - 1;
         l_phase = NPHASE - 1;
         l_k = l_nk - 1;
-        l_pa -= BK * 2;
-        l_pb -= BK * 2;
+        l_pa -= ROWB;
+        l_pb -= ROWB;
       }
     }
   };
 
   // ---- fragment read offsets ----------------------------------------------------------
-  // A fragment (mt, ks): row = wm*64 + mt*32 + (lane & 31), chunk = 2 ks + (lane >> 5)
+  // A fragment (mt, ks): row = wm*32*MI + mt*32 + (lane & 31), chunk = 2 ks + (lane >> 5)
   const int frow = lane & 31;
-  const int fsw = (frow >> 1) & 7;
-  int fk[4];
+  const int fsw = (frow >> Cfg::SW_SHIFT) & (CH - 1);
+  int fk[KS];
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) fk[ks] = ((2 * ks + (lane >> 5)) ^ fsw) << 4;
-  const int a_base = (wm * 64 + frow) * (BK * 2);
-  const int b_base = A_STAGE_BYTES + (wn * 128 + frow) * (BK * 2);
+  for (int ks = 0; ks < KS; ++ks) fk[ks] = ((2 * ks + (lane >> 5)) ^ fsw) << 4;
+  const int a_base = (wm * 32 * MI + frow) * ROWB;
+  const int b_base = A_STAGE_BYTES + (wn * 128 + frow) * ROWB;
 
-  AccTile acc0, acc1;
-  zero_acc(acc0);
-  if (NPHASE > 1) zero_acc(acc1);
+  Acc acc0, acc1;
+  Cfg::zero(acc0);
+  if (NPHASE > 1) Cfg::zero(acc1);
 
-  int stage = 0;       // LDS stage of the k-step being consumed
+  int stage = 0;            // LDS stage of the k-step being consumed
+  int fill = NST - 1;       // LDS stage being refilled (released by the previous k-step)
 
   auto read_frags = [&](int st, int ks, bf16x8 (&af)[MI], bf16x8 (&bfr)[NI]) {
     const char* base = smem + st * STAGE_BYTES;
 #pragma unroll
-    for (int mt = 0; mt < MI; ++mt) af[mt] = *(const bf16x8*)(base + a_base + mt * 32 * BK * 2 + fk[ks]);
+    for (int mt = 0; mt < MI; ++mt) af[mt] = *(const bf16x8*)(base + a_base + mt * 32 * ROWB + fk[ks]);
 #pragma unroll
-    for (int nt = 0; nt < NI; ++nt) bfr[nt] = *(const bf16x8*)(base + b_base + nt * 32 * BK * 2 + fk[ks]);
+    for (int nt = 0; nt < NI; ++nt) bfr[nt] = *(const bf16x8*)(base + b_base + nt * 32 * ROWB + fk[ks]);
   };
-  auto mma = [&](AccTile& acc, const bf16x8 (&af)[MI], const bf16x8 (&bfr)[NI]) {
+  auto mma = [&](Acc& acc, const bf16x8 (&af)[MI], const bf16x8 (&bfr)[NI]) {
 #pragma unroll
     for (int mt = 0; mt < MI; ++mt)
 #pragma unroll
       for (int nt = 0; nt < NI; ++nt)
         acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mt], bfr[nt], acc[mt][nt], 0, 0, 0);
   };
-
-  // Fragments of sub-step 0 of the k-step about to be consumed; kept across k-steps.
-  bf16x8 fa0[MI], fb0[NI];
-
-  // One k-step.  On entry fa0/fb0 hold sub-step 0.  The barrier sits before the last group
-  // of MFMAs: after it the stage just read is refilled with the k-step three ahead and the
-  // first fragments of the next k-step are read, all in the shadow of that last group.
-  auto kstep = [&](AccTile& acc) {
-    bf16x8 fa1[MI], fb1[NI];
-    const int next = stage == 2 ? 0 : stage + 1;
-    read_frags(stage, 1, fa1, fb1);
-    mma(acc, fa0, fb0);
-    __builtin_amdgcn_sched_barrier(0);
-    read_frags(stage, 2, fa0, fb0);
-    mma(acc, fa1, fb1);
-    __builtin_amdgcn_sched_barrier(0);
-    read_frags(stage, 3, fa1, fb1);
-    mma(acc, fa0, fb0);
-    __builtin_amdgcn_sched_barrier(0);
-    // k-steps g, g+1, g+2 are in flight; at most the 12 loads of g+2 may still be pending
-    asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    issue_loads(stage);
-    read_frags(next, 0, fa0, fb0);
-    mma(acc, fa1, fb1);
+  // Order inside one sub-step: fragment reads first (two per MFMA), then one load per MFMA.
+  auto schedule_substep = [&]() {
+    constexpr int n_mfma = MI * NI, n_ds = MI + NI;
+    constexpr int ds_slots = (n_ds + 1) / 2;
+    static_assert(ds_slots + LPS <= n_mfma, "not enough MFMAs to cover the memory instructions");
 #pragma unroll
-    for (int i = 0; i < 3; ++i) {
+    for (int i = 0; i < ds_slots; ++i) {
       __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
       __builtin_amdgcn_sched_group_barrier(SG_DSREAD, 2, 0);
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < LPS; ++i) {
       __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(SG_VMEM, 3, 0);
+      __builtin_amdgcn_sched_group_barrier(SG_VMEM, 1, 0);
     }
-    __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(SG_MFMA, n_mfma - ds_slots - LPS, 0);
     __builtin_amdgcn_sched_barrier(0);
+  };
+
+  // Fragments of sub-step 0 of the k-step about to be consumed; kept across k-steps.
+  bf16x8 fa0[MI], fb0[NI];
+
+  // One k-step.  On entry fa0/fb0 hold sub-step 0.
+  auto kstep = [&](Acc& acc) {
+    bf16x8 fa1[MI], fb1[NI];
+    const int next = stage == NST - 1 ? 0 : stage + 1;
+#pragma unroll
+    for (int ks = 0; ks < KS - 1; ++ks) {
+      // even sub-steps multiply (fa0, fb0) and fetch into (fa1, fb1); odd ones the reverse
+      if (ks % 2 == 0) {
+        read_frags(stage, ks + 1, fa1, fb1);
+        issue_loads(fill, ks * LPS < LOADS ? ks * LPS : LOADS, (ks + 1) * LPS < LOADS ? (ks + 1) * LPS : LOADS);
+        mma(acc, fa0, fb0);
+      } else {
+        read_frags(stage, ks + 1, fa0, fb0);
+        issue_loads(fill, ks * LPS < LOADS ? ks * LPS : LOADS, (ks + 1) * LPS < LOADS ? (ks + 1) * LPS : LOADS);
+        mma(acc, fa1, fb1);
+      }
+      schedule_substep();
+    }
+    // k-step g+1 must have landed; after the barrier nobody reads stage `stage` any more
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(Cfg::WAIT_STEADY) : "memory");
+    // last sub-step (KS-1, odd): multiplies (fa1, fb1), fetches sub-step 0 of the next k-step
+    issue_loads(fill, Cfg::LOADS_BEFORE_BARRIER, LOADS);
+    read_frags(next, 0, fa0, fb0);
+    mma(acc, fa1, fb1);
+    schedule_substep();
     advance();
+    fill = stage;
     stage = next;
   };
 
-  // ---- prologue: three k-steps in flight, first fragments read ------------------------------
-  issue_loads(0);
-  advance();
-  issue_loads(1);
-  advance();
-  issue_loads(2);
-  advance();
-  asm volatile("s_waitcnt vmcnt(24)\n\ts_barrier" ::: "memory");
+  // ---- prologue: NST-1 k-steps in flight, first fragments read -------------------------------
+#pragma unroll
+  for (int i = 0; i < NST - 1; ++i) {
+    issue_loads(i, 0, LOADS);
+    advance();
+  }
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(Cfg::WAIT_PROLOGUE) : "memory");
   read_frags(0, 0, fa0, fb0);
 
   for (int c_item = 0; c_item < n_items; ++c_item) {
@@ -284,8 +312,8 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
     if (NPHASE > 1)
       for (int k = 0; k < ci.nk1; ++k) kstep(acc1);
     epi.end_item(ci, acc0, acc1);
-    zero_acc(acc0);
-    if (NPHASE > 1) zero_acc(acc1);
+    Cfg::zero(acc0);
+    if (NPHASE > 1) Cfg::zero(acc1);
   }
   // the loads issued past the end still target this workgroup's LDS: let them land
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
