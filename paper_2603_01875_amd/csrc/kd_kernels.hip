@@ -13,17 +13,21 @@
 #include "kd_mfma.hpp"
 #include "kd_launch.h"
 
-#ifndef KD_GEMM_MI
-#define KD_GEMM_MI 4
-#define KD_GEMM_BK 32
-#define KD_GEMM_NST 4
+// tile configurations (overridable for tuning experiments)
+#ifndef KD_LOGIT_CFG
+#define KD_LOGIT_CFG 2, 2, 4, 64, 3     // MI, NI, WN, BK, NST: 128 x 256 tile, 8 waves
+#endif
+#ifndef KD_GEMM_CFG
+#define KD_GEMM_CFG 2, 4, 2, 64, 3      // 128 x 256 tile, 4 waves
 #endif
 
 namespace kd {
 
-typedef TileCfg<2, 64, 3> LCfg;   // logit tiles: two accumulators of 128 x 256, three LDS stages
-typedef TileCfg<KD_GEMM_MI, KD_GEMM_BK, KD_GEMM_NST> GCfg;   // backward products: one accumulator
+typedef TileCfg<KD_LOGIT_CFG> LCfg;   // logit tiles: two accumulators per tile
+typedef TileCfg<KD_GEMM_CFG> GCfg;    // backward products: one accumulator
 constexpr int BK = LCfg::BK;
+constexpr int NI = LCfg::NI;
+static_assert(LCfg::BM == kTileM && BN == kTileN && GCfg::BM == kGemmTileM, "planner and kernels disagree");
 constexpr int BM = LCfg::BM;
 constexpr int MI = LCfg::MI;
 typedef LCfg::Acc AccTile;
@@ -317,10 +321,11 @@ struct GradEpi {
 // ------------------------------------------------------------------------------------------
 // logit kernels
 // ------------------------------------------------------------------------------------------
-#define KD_KERNEL __global__ __launch_bounds__(NTHREADS, 1)
+#define KD_LOGIT_KERNEL __global__ __launch_bounds__(LCfg::NT)
+#define KD_GEMM_KERNEL __global__ __launch_bounds__(GCfg::NT)
 
 template <int KIND>
-KD_KERNEL void stats_kernel(const LogitArgs a) {
+KD_LOGIT_KERNEL void stats_kernel(const LogitArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   SplitWork work(a);
   StatsEpi<KIND> epi(a.c);
@@ -328,7 +333,7 @@ KD_KERNEL void stats_kernel(const LogitArgs a) {
   epi.write(a, work.tt, work.split);
 }
 
-KD_KERNEL void jsd_rows_kernel(const LogitArgs a) {
+KD_LOGIT_KERNEL void jsd_rows_kernel(const LogitArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   SplitWork work(a);
   JsdEpi epi(a, work.tt);
@@ -337,7 +342,7 @@ KD_KERNEL void jsd_rows_kernel(const LogitArgs a) {
 }
 
 template <int KIND>
-KD_KERNEL void grad_kernel(const LogitArgs a) {
+KD_LOGIT_KERNEL void grad_kernel(const LogitArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   ChunkWork work(a);
   GradEpi<KIND> epi(a);
@@ -398,7 +403,7 @@ struct StoreEpi {
   __device__ void begin_item(const WorkItem&) {}
   __device__ void end_item(const WorkItem& it, GCfg::Acc& acc, GCfg::Acc&) {
 #pragma unroll
-    for (int nt = 0; nt < NI; ++nt) {
+    for (int nt = 0; nt < GCfg::NI; ++nt) {
       const int nl = GCfg::acc_n(wn, nt, lane);
       if (nl >= it.b_rows) continue;
       const int64_t row = (int64_t)(it.n0 + nl) * a.ldo + (int64_t)it.aux * a.out_split_stride;
@@ -430,7 +435,7 @@ struct StoreEpi {
   }
 };
 
-KD_KERNEL void gemm_kernel(const GemmArgs a) {
+KD_GEMM_KERNEL void gemm_kernel(const GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   GemmWork work(a);
   StoreEpi epi(a);
@@ -563,11 +568,12 @@ static int largest_divisor_le(int n, int cap) {
 }
 
 template <class Kern>
-static hipError_t launch_big(Kern kern, int grid, int smem_bytes, hipStream_t st, const void* args_ptr) {
+static hipError_t launch_big(Kern kern, int grid, int threads, int smem_bytes, hipStream_t st,
+                             const void* args_ptr) {
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes);
   if (e != hipSuccess) return e;
   void* params[] = {const_cast<void*>(args_ptr)};
-  return hipLaunchKernel((const void*)kern, dim3(grid), dim3(NTHREADS), params, smem_bytes, st);
+  return hipLaunchKernel((const void*)kern, dim3(grid), dim3(threads), params, smem_bytes, st);
 }
 
 static LogitArgs make_logit_args(const Problem& p) {
@@ -591,9 +597,9 @@ hipError_t launch_stats(const Problem& p, hipStream_t st) {
   a.partials = p.partials;
   const int grid = p.n_tt * p.n_split;
   switch (p.kind) {
-    case 0: return launch_big(stats_kernel<0>, grid, LCfg::SMEM_BYTES, st, &a);
-    case 1: return launch_big(stats_kernel<1>, grid, LCfg::SMEM_BYTES, st, &a);
-    default: return launch_big(stats_kernel<2>, grid, LCfg::SMEM_BYTES, st, &a);
+    case 0: return launch_big(stats_kernel<0>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
+    case 1: return launch_big(stats_kernel<1>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
+    default: return launch_big(stats_kernel<2>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
   }
 }
 
@@ -603,7 +609,7 @@ hipError_t launch_jsd_rows(const Problem& p, hipStream_t st) {
   a.ba = largest_divisor_le(p.n_tt, 4);
   a.bb = largest_divisor_le(p.n_split, 8);
   a.partials = p.partials;
-  return launch_big(jsd_rows_kernel, p.n_tt * p.n_split, LCfg::SMEM_BYTES, st, &a);
+  return launch_big(jsd_rows_kernel, p.n_tt * p.n_split, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
 }
 
 hipError_t launch_combine(const Problem& p, hipStream_t st) {
@@ -636,9 +642,9 @@ hipError_t launch_grad_chunk(const Problem& p, int v0, int width, hipStream_t st
   const int tiles = p.n_tt * a.n_vt;
   int grid = tiles < p.n_cu ? tiles : p.n_cu;
   switch (p.kind) {
-    case 0: return launch_big(grad_kernel<0>, grid, LCfg::SMEM_BYTES, st, &a);
-    case 1: return launch_big(grad_kernel<1>, grid, LCfg::SMEM_BYTES, st, &a);
-    default: return launch_big(grad_kernel<2>, grid, LCfg::SMEM_BYTES, st, &a);
+    case 0: return launch_big(grad_kernel<0>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
+    case 1: return launch_big(grad_kernel<1>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
+    default: return launch_big(grad_kernel<2>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
   }
 }
 
@@ -663,7 +669,7 @@ hipError_t launch_gemm(const GemmDesc& d, int n_cu, hipStream_t st) {
   a.n_nt = (d.N + BN - 1) / BN;
   const int tiles = a.n_mt * a.n_nt * a.n_ksplit;
   const int grid = tiles < n_cu ? tiles : n_cu;
-  return launch_big(gemm_kernel, grid, GCfg::SMEM_BYTES, st, &a);
+  return launch_big(gemm_kernel, grid, GCfg::NT, GCfg::SMEM_BYTES, st, &a);
 }
 
 hipError_t launch_gradh_finish(const Problem& p, hipStream_t st) {

@@ -24,21 +24,27 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 
-constexpr int NTHREADS = 256;    // 4 waves, 2 (M) x 2 (N)
-constexpr int NI = 4;            // 32-row MFMA blocks per wave along N
-constexpr int BN = 256;          // tile rows of B (MFMA N axis): 2 waves x NI x 32
+constexpr int BN = 256;          // tile rows of B (MFMA N axis)
 
-// Tile shape and pipeline depth.  MI 32-row MFMA blocks per wave along M give a tile of
-// BM = 64 MI rows of A; a k-step covers BK elements (32 or 64); NST LDS stages of one
-// k-step each.
+// Tile shape and pipeline depth.  A workgroup is 2 (M) x WN (N) waves; a wave owns MI x NI
+// MFMA blocks of 32 x 32, so the tile has BM = 64 MI rows of A and BN = 32 NI WN = 256
+// rows of B.  A k-step covers BK elements (32 or 64); NST LDS stages of one k-step each.
+// WN = 2 (4 waves, one per SIMD, up to 512 registers each) suits one big accumulator;
+// WN = 4 (8 waves, two per SIMD, 256 registers each) gives every SIMD a second
+// instruction stream: a wave can keep only one ds_read_b128 per 32 cycles in flight, and
+// the second wave also covers the other one's barrier and memory waits.
 //
 // LDS tile layout: row r occupies ROWB = 2 BK bytes; its CH = BK/8 16-byte chunks are
 // permuted by XOR with a few row bits so that 16 lanes reading the same logical chunk of
 // 16 consecutive rows hit 16 distinct 16-byte bank groups (conflict-free ds_read_b128),
 // while the direct loads still write each wave's 1 KiB linearly.
-template <int MI_, int BK_, int NST_>
+template <int MI_, int NI_, int WN_, int BK_, int NST_>
 struct TileCfg {
   static constexpr int MI = MI_;
+  static constexpr int NI = NI_;
+  static constexpr int WN = WN_;
+  static constexpr int NT = 128 * WN_;                     // threads per workgroup
+  static_assert(32 * NI_ * WN_ == BN, "tile rows of B");
   static constexpr int BK = BK_;
   static constexpr int NST = NST_;
   static constexpr int KS = BK_ / 16;                      // MFMA sub-steps per k-step
@@ -46,7 +52,7 @@ struct TileCfg {
   static constexpr int ROWB = BK_ * 2;
   static constexpr int CH = BK_ / 8;
   static constexpr int SW_SHIFT = BK_ == 64 ? 1 : 2;       // swizzle = (row >> SW_SHIFT) & (CH - 1)
-  static constexpr int ROWS_PER_LOAD = NTHREADS / CH;      // tile rows covered by one load instruction
+  static constexpr int ROWS_PER_LOAD = NT / CH;      // tile rows covered by one load instruction
   static constexpr int A_LOADS = BM / ROWS_PER_LOAD;       // 16-byte loads per thread per k-step
   static constexpr int B_LOADS = BN / ROWS_PER_LOAD;
   static constexpr int LOADS = A_LOADS + B_LOADS;
@@ -70,7 +76,7 @@ struct TileCfg {
     return wm * (32 * MI_) + mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
   }
   static __device__ __forceinline__ int acc_n(int wn, int nt, int lane) {
-    return wn * 128 + nt * 32 + (lane & 31);
+    return wn * (32 * NI_) + nt * 32 + (lane & 31);
   }
   static __device__ __forceinline__ void zero(Acc& acc) {
 #pragma unroll
@@ -136,7 +142,7 @@ template <int NPHASE, class Cfg, class Work, class Epi>
 __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
                                           const int lda0, const int lda1, const int ldb0, const int ldb1,
                                           char* smem) {
-  constexpr int MI = Cfg::MI, NST = Cfg::NST, BK = Cfg::BK, KS = Cfg::KS, CH = Cfg::CH;
+  constexpr int MI = Cfg::MI, NI = Cfg::NI, NST = Cfg::NST, KS = Cfg::KS, CH = Cfg::CH;
   constexpr int A_LOADS = Cfg::A_LOADS, LOADS = Cfg::LOADS, LPS = Cfg::LOADS_PER_SUB;
   constexpr int A_STAGE_BYTES = Cfg::A_STAGE_BYTES, STAGE_BYTES = Cfg::STAGE_BYTES;
   constexpr int ROWB = Cfg::ROWB;
@@ -151,7 +157,7 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
   if (n_items == 0) return;
 
   // ---- load cursor ------------------------------------------------------------------
-  // Load j of lane (wave w, lane l) fills the 16-byte LDS slot j*256 + w*64 + l of the
+  // Load j of lane (wave w, lane l) fills the 16-byte LDS slot j*NT + w*64 + l of the
   // stage (A region first, then B): tile row j*ROWS_PER_LOAD + tid/CH, physical chunk
   // tid%CH.  The chunk it fetches from global memory is the logical one that the XOR
   // layout keeps in that slot.
@@ -184,7 +190,7 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
 #pragma unroll
     for (int j = j0; j < j1; ++j)
       __builtin_amdgcn_global_load_lds((const void*)((j < A_LOADS ? l_pa : l_pb) + loff[j]),
-                                       (lds_void_t*)(sbase + j * 4096), 16, 0, 0);
+                                       (lds_void_t*)(sbase + j * (Cfg::NT * 16)), 16, 0, 0);
   };
   auto advance = [&]() {
     l_pa += ROWB;
@@ -221,7 +227,7 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) fk[ks] = ((2 * ks + (lane >> 5)) ^ fsw) << 4;
   const int a_base = (wm * 32 * MI + frow) * ROWB;
-  const int b_base = A_STAGE_BYTES + (wn * 128 + frow) * ROWB;
+  const int b_base = A_STAGE_BYTES + (wn * 32 * NI + frow) * ROWB;
 
   Acc acc0, acc1;
   Cfg::zero(acc0);
