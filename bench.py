@@ -47,6 +47,8 @@ def main():
     ap.add_argument("--workload", default="fkl_bf16")
     ap.add_argument("--cpu-rows", type=int, default=64, help="tokens of the oracle sample (0 = skip)")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "traffic.json"))
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (scale for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (one worker's share of the data-parallel "
@@ -76,6 +78,13 @@ def main():
 
     def step():
         K.kd_loss_fwd_bwd_raw(p, dev["h_t"], dev["W_t"], dev["h_s"], dev["W_s"], mask, loss, ptl, gh, gW, ws)
+
+    if args.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                 # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

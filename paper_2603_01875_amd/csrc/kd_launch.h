@@ -9,7 +9,10 @@ namespace kd {
 constexpr int kNumCU = 256;            // MI355X: 8 XCDs x 32 CUs; persistent grids are sized for it
 constexpr int kTileM = 128;            // vocabulary rows per logit tile
 constexpr int kTileN = 256;            // token rows per logit tile
-constexpr int kGemmTileM = 128;        // rows of the first operand per tile of the backward products
+#ifndef KD_GEMM_TILE_M
+#define KD_GEMM_TILE_M 128
+#endif
+constexpr int kGemmTileM = KD_GEMM_TILE_M;        // rows of the first operand per tile of the backward products
 
 // Everything a launch needs, resolved by the planner in kd_api.hip.
 struct Problem {
