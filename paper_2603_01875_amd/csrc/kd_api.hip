@@ -15,6 +15,7 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 struct Layout {
   size_t rowinfo, row_loss, partials, h_sT, W_sT, dz, dzT, gh32, total;
+  size_t prep_h_t, prep_W_t, prep_h_s, prep_W_s;   // re-packed operands (only when needed)
 };
 
 kd_status check_params(const kd_loss_params* p) {
@@ -30,8 +31,6 @@ kd_status check_params(const kd_loss_params* p) {
   if (p->kind == KD_JSD && !(p->beta > 0.f && p->beta < 1.f)) return KD_ERR_PARAM;
   if (p->accumulate_grad_W != 0 && p->accumulate_grad_W != 1) return KD_ERR_PARAM;
   if (p->reserved != 0) return KD_ERR_PARAM;
-  if (p->in_dtype != KD_BF16) return KD_ERR_UNSUPPORTED;
-  if (p->H_t % 64 || p->H_s % 64) return KD_ERR_UNSUPPORTED;   // k-steps are whole 64-element blocks
   if (p->w_layout != KD_W_VH) return KD_ERR_UNSUPPORTED;
   return KD_OK;
 }
@@ -43,6 +42,14 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward) {
   q.grad_f32 = p->grad_dtype == KD_F32;
   q.accumulate_grad_W = p->accumulate_grad_W;
   q.n_cu = kd::kNumCU;
+  // Operands as the kernels want them: bf16, K-contiguous, K a multiple of 64.  fp32 inputs are
+  // split into bf16 high and low parts laid side by side along K (three products recover all
+  // but the low x low term); bf16 inputs with an odd hidden size are zero-padded along K.
+  q.in_f32 = p->in_dtype == KD_F32;
+  q.K_t = (int)round_up(q.in_f32 ? 3 * q.H_t : q.H_t, 64);
+  q.K_s = (int)round_up(q.in_f32 ? 3 * q.H_s : q.H_s, 64);
+  q.prep_t = q.in_f32 || q.K_t != q.H_t;
+  q.prep_s = q.in_f32 || q.K_s != q.H_s;
   q.T_pad = (int)round_up(q.T, kd::kTileN);
   q.n_tt = q.T_pad / kd::kTileN;
   q.n_vt = (int)((q.V + kd::kTileM - 1) / kd::kTileM);
@@ -79,6 +86,15 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward) {
   L.rowinfo = take((size_t)q.T_pad * 16);
   L.row_loss = take((size_t)q.T_pad * 4);
   L.partials = take((size_t)q.n_split * 4 * 5 * q.T_pad * 4);
+  L.prep_h_t = L.prep_W_t = L.prep_h_s = L.prep_W_s = 0;
+  if (q.prep_t) {
+    L.prep_h_t = take((size_t)q.T * q.K_t * 2);
+    L.prep_W_t = take((size_t)q.V * q.K_t * 2);
+  }
+  if (q.prep_s) {
+    L.prep_h_s = take((size_t)q.T * q.K_s * 2);
+    L.prep_W_s = take((size_t)q.V * q.K_s * 2);
+  }
   if (with_backward) {
     L.h_sT = take((size_t)q.H_s * q.T_pad * 2);
     L.W_sT = take((size_t)q.H_s * q.V_c * 2);
@@ -101,7 +117,12 @@ void carve(Problem& q, const Layout& L, void* ws) {
   q.dz = b + L.dz;
   q.dzT = b + L.dzT;
   q.gh32 = reinterpret_cast<float*>(b + L.gh32);
+  q.user_h_t = q.h_t; q.user_W_t = q.W_t; q.user_h_s = q.h_s; q.user_W_s = q.W_s;
+  if (q.prep_t) { q.h_t = b + L.prep_h_t; q.W_t = b + L.prep_W_t; }
+  if (q.prep_s) { q.h_s = b + L.prep_h_s; q.W_s = b + L.prep_W_s; }
 }
+
+
 
 // Benchmark aid: bracket the launches of one kernel family with caller-supplied events.
 struct ProfileHook {
@@ -134,7 +155,24 @@ struct ProfileScope {
     if ((expr) != hipSuccess) return KD_ERR_LAUNCH; \
   } while (0)
 
+// Re-pack the operands that need it (fp32 split / K padding) into the workspace.
+kd_status prepare_operands(const Problem& q, hipStream_t st) {
+  if (q.prep_t) {
+    KD_TRY(kd::launch_prepare(q.user_h_t, q.in_f32, q.T, q.H_t, const_cast<void*>(q.h_t), q.K_t, 2, st));
+    KD_TRY(kd::launch_prepare(q.user_W_t, q.in_f32, q.V, q.H_t, const_cast<void*>(q.W_t), q.K_t, 1, st));
+  }
+  if (q.prep_s) {
+    KD_TRY(kd::launch_prepare(q.user_h_s, q.in_f32, q.T, q.H_s, const_cast<void*>(q.h_s), q.K_s, 2, st));
+    KD_TRY(kd::launch_prepare(q.user_W_s, q.in_f32, q.V, q.H_s, const_cast<void*>(q.W_s), q.K_s, 1, st));
+  }
+  return KD_OK;
+}
+
 kd_status run_forward(const Problem& q, hipStream_t st) {
+  {
+    kd_status ps = prepare_operands(q, st);
+    if (ps != KD_OK) return ps;
+  }
   {
     ProfileScope ps(KD_PROF_STATS, st);
     KD_TRY(kd::launch_stats(q, st));
@@ -226,7 +264,7 @@ kd_status kd_loss_fwd_bwd(const kd_loss_params* params, const void* h_t, const v
   if (s != KD_OK) return s;
 
   // h_s^T [H_s][T_pad] once (token axis zero-padded): the K-contiguous operand of grad_W_s
-  KD_TRY(kd::launch_transpose(q.h_s, q.H_s, q.T, q.H_s, q.h_sT, q.T_pad, q.T_pad, st));
+  KD_TRY(kd::launch_transpose(q.h_s, q.K_s, q.T, q.H_s, q.h_sT, q.T_pad, q.T_pad, st));
 
   const size_t gsz = q.grad_f32 ? 4 : 2;
   bool first = true;
@@ -237,7 +275,7 @@ kd_status kd_loss_fwd_bwd(const kd_loss_params* params, const void* h_t, const v
       KD_TRY(kd::launch_grad_chunk(q, (int)v0, width, st));
     }
     // W_s[chunk]^T [H_s][V_c]: the K-contiguous operand of grad_h_s
-    KD_TRY(kd::launch_transpose(static_cast<const char*>(q.W_s) + (size_t)v0 * q.H_s * 2, q.H_s, width, q.H_s,
+    KD_TRY(kd::launch_transpose(static_cast<const char*>(q.W_s) + (size_t)v0 * q.K_s * 2, q.K_s, width, q.H_s,
                                 q.W_sT, q.V_c, (int)round_up(width, 64), st));
     kd::GemmDesc gw{};   // grad_W_s[v][h] = sum_t h_sT[h][t] dzT[v][t]
     gw.A = q.h_sT; gw.lda = q.T_pad; gw.M = q.H_s;

@@ -55,7 +55,7 @@ __device__ __forceinline__ void block_decode(int q, int na, int ba, int bb, int&
 
 struct LogitArgs {
   const bf16_t* W_s; const bf16_t* h_s; const bf16_t* W_t; const bf16_t* h_t;
-  int T, V, H_s, H_t;
+  int T, V, H_s, H_t;  // H_*: contraction length and row stride of the (re-packed) operands
   int n_tt;            // token tiles of BN rows
   int vt0, n_vt;       // vocabulary tiles [vt0, vt0 + n_vt) of BM rows handled by this launch
   int n_split;         // stats kernels: vocabulary splits (grid = n_tt * n_split)
@@ -542,6 +542,28 @@ __global__ void transpose_kernel(const bf16_t* src, int64_t ld_src, int R, int C
   }
 }
 
+// Re-pack one operand as bf16 [R][K]: plain copy (bf16 source) or the high / low bf16 parts of an
+// fp32 source laid side by side along K, zero-padded up to K.
+//   split_mode 1 (heads):         [hi | hi | lo]
+//   split_mode 2 (hidden states): [hi | lo | hi]
+// so that sum_k A'[m][k] B'[n][k] = hi.hi + hi.lo + lo.hi.
+__global__ void prepare_kernel(const void* src, int src_f32, int R, int H, bf16_t* dst, int K, int split_mode) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)R * K) return;
+  const int r = (int)(i / K), c = (int)(i % K);
+  bf16_t v = (bf16_t)0.f;
+  if (!src_f32) {
+    if (c < H) v = ((const bf16_t*)src)[(int64_t)r * H + c];
+  } else if (c < 3 * H) {
+    const int part = c / H, col = c - part * H;
+    const float x = ((const float*)src)[(int64_t)r * H + col];
+    const bf16_t hi = (bf16_t)x;
+    const bool want_lo = (split_mode == 1 && part == 2) || (split_mode == 2 && part == 1);
+    v = want_lo ? (bf16_t)(x - (float)hi) : hi;
+  }
+  dst[i] = v;
+}
+
 // grad_h_s = sum over split-K parts of the fp32 partial sums, converted to the output dtype.
 __global__ void gradh_finish_kernel(const float* parts, int n_parts, int64_t n, int out_f32, void* out) {
   const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
@@ -580,7 +602,7 @@ static LogitArgs make_logit_args(const Problem& p) {
   LogitArgs a{};
   a.W_s = (const bf16_t*)p.W_s; a.h_s = (const bf16_t*)p.h_s;
   a.W_t = (const bf16_t*)p.W_t; a.h_t = (const bf16_t*)p.h_t;
-  a.T = p.T; a.V = p.V; a.H_s = p.H_s; a.H_t = p.H_t;
+  a.T = p.T; a.V = p.V; a.H_s = p.K_s; a.H_t = p.K_t;   // contraction lengths = row strides
   a.n_tt = p.n_tt;
   a.c = 1.4426950408889634f / p.tau;
   a.beta = p.beta;
@@ -670,6 +692,14 @@ hipError_t launch_gemm(const GemmDesc& d, int n_cu, hipStream_t st) {
   const int tiles = a.n_mt * a.n_nt * a.n_ksplit;
   const int grid = tiles < n_cu ? tiles : n_cu;
   return launch_big(gemm_kernel, grid, GCfg::NT, GCfg::SMEM_BYTES, st, &a);
+}
+
+hipError_t launch_prepare(const void* src, int src_f32, int R, int H, void* dst, int K, int split_mode,
+                          hipStream_t st) {
+  const int64_t n = (int64_t)R * K;
+  hipLaunchKernelGGL(prepare_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, src, src_f32, R, H,
+                     (bf16_t*)dst, K, split_mode);
+  return hipGetLastError();
 }
 
 hipError_t launch_gradh_finish(const Problem& p, hipStream_t st) {

@@ -21,7 +21,10 @@ struct Problem {
   float tau, beta;
   int grad_f32;
   int accumulate_grad_W;
-  const void *h_t, *W_t, *h_s, *W_s;
+  const void *h_t, *W_t, *h_s, *W_s;                   // bf16 [rows][K_t or K_s] as the kernels read them
+  const void *user_h_t, *user_W_t, *user_h_s, *user_W_s;  // the caller's arrays
+  int in_f32, prep_t, prep_s;   // inputs are fp32; teacher / student operands are re-packed into the workspace
+  int K_t, K_s;                 // contraction lengths of the (re-packed) logit operands, multiples of 64
   const uint8_t* mask;
   float* loss;
   float* per_token_loss;
@@ -61,5 +64,8 @@ hipError_t launch_transpose(const void* src, int64_t ld_src, int R, int C, void*
                             hipStream_t st);
 hipError_t launch_gemm(const GemmDesc& d, int n_cu, hipStream_t st);
 hipError_t launch_gradh_finish(const Problem& p, hipStream_t st);
+// dst bf16 [R][K]: mode 0 = copy, 1 = fp32 split as [hi|hi|lo], 2 = fp32 split as [hi|lo|hi]; zero-padded to K
+hipError_t launch_prepare(const void* src, int src_f32, int R, int H, void* dst, int K, int split_mode,
+                          hipStream_t st);
 
 }  // namespace kd

@@ -59,12 +59,19 @@ def test_workspace_is_far_below_T_times_V():
     (dict(T=0), 2), (dict(V=-8), 2), (dict(H_t=100), 3), (dict(V=151937), 3),
     (dict(tau=0.0), 4), (dict(tau=float("nan")), 4), (dict(kind=7), 4),
     (dict(kind=K.JSD, beta=0.0), 4), (dict(kind=K.JSD, beta=1.0), 4), (dict(in_dtype=5), 4),
-    (dict(w_layout=K.W_HV), 6), (dict(H_s=72), 6),
+    (dict(w_layout=K.W_HV), 6),
 ])
 def test_bad_params_are_rejected(kw, status):
     with pytest.raises(K.KdLossError) as e:
         K.kd_loss_workspace_size(_ws(**kw))
     assert e.value.status == status
+
+
+def test_fp32_and_odd_hidden_sizes_need_more_workspace():
+    base = K.kd_loss_workspace_size(K.make_params(512, 256, 128, 4096))
+    odd = K.kd_loss_workspace_size(K.make_params(512, 200, 72, 4096))          # K padded to 256 / 128
+    f32 = K.kd_loss_workspace_size(K.make_params(512, 256, 128, 4096, in_dtype=K.F32))
+    assert odd > base and f32 > odd
 
 
 def test_beta_ignored_for_kl():

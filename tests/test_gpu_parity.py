@@ -97,3 +97,30 @@ def test_peaked_teacher_is_stable():
     cfg = I.scaled(I.workload("long_peaked"), batch=1, seq=256, H_t=5120, H_s=256, V=4096)
     data = I.generate(cfg)
     G.check(G.run_gpu(cfg, data), G.run_oracle(cfg, data), "peaked")
+
+
+def test_tiny_fp32_workload():
+    # the fp32 correctness configuration, at its full size: T=128, H_t=256, H_s=128, V=4096
+    cfg = I.workload("tiny_fkl_f32")
+    data = I.generate(cfg)
+    from paper_2603_01875_amd import kdloss as K
+    out = G.run_gpu(cfg, data)                      # fp32 inputs -> fp32 gradients
+    ref = G.run_oracle(cfg, data)
+    G.check(out, ref, "tiny fp32")
+    assert abs(ref["loss"] - 0.0754) < 0.004        # Gaussian-regime value for sigma = 0.32 / 0.23
+    out16 = G.run_gpu(cfg, data, grad_dtype=K.BF16)
+    G.check(out16, ref, "tiny fp32, bf16 grads")
+
+
+@pytest.mark.parametrize("name", ["fkl_bf16", "jsd_bf16"])
+def test_hidden_sizes_not_multiples_of_64(name):
+    cfg = I.scaled(I.workload(name), batch=2, seq=140, H_t=200, H_s=72, V=1032)
+    data = I.generate(cfg)
+    G.check(G.run_gpu(cfg, data), G.run_oracle(cfg, data), f"odd hidden {name}")
+
+
+def test_fp32_inputs_other_kinds():
+    for name in ("rkl_bf16", "jsd_bf16"):
+        cfg = I.scaled(I.workload(name), batch=2, seq=100, H_t=96, H_s=40, V=520, dtype=I.F32)
+        data = I.generate(cfg)
+        G.check(G.run_gpu(cfg, data), G.run_oracle(cfg, data), f"fp32 {name}")
