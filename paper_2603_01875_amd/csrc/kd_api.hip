@@ -53,15 +53,18 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward) {
   q.T_pad = (int)round_up(q.T, kd::kTileN);
   q.n_tt = q.T_pad / kd::kTileN;
   q.n_vt = (int)((q.V + kd::kTileM - 1) / kd::kTileM);
+  // vocabulary splits of the statistics passes: enough workgroups to fill the chip, and at least 8
+  // so that the 32 workgroups co-resident on an XCD form a 4 (token) x 8 (vocabulary) block
   int ns = (q.n_cu + q.n_tt - 1) / q.n_tt;
+  if (ns < 8) ns = 8;
   if (ns > q.n_vt) ns = q.n_vt;
   if (ns < 1) ns = 1;
   q.n_split = ns;
 
   // vocabulary chunk of the backward pass: the largest power of two (1024..16384 columns)
-  // whose [T_pad, V_c] bf16 staging buffer stays within 128 MiB
+  // whose [T_pad, V_c] bf16 staging buffer stays within 512 MiB
   int64_t vc = 16384;
-  while (vc > 1024 && (int64_t)q.T_pad * vc * 2 > (128ll << 20)) vc >>= 1;
+  while (vc > 1024 && (int64_t)q.T_pad * vc * 2 > (512ll << 20)) vc >>= 1;
   if (const char* e = std::getenv("KD_VOCAB_CHUNK")) {
     const long v = std::atol(e);
     if (v >= 256 && v <= (1 << 20)) vc = round_up(v, 256);

@@ -363,6 +363,7 @@ struct GemmArgs {
   int out_f32;         // 1: float, 0: bf16
   int accumulate;      // 1: out += D
   int n_mt, n_nt;
+  int ba, bb;          // block shape of the work map (ba | n_mt, bb | n_nt)
 };
 
 struct GemmWork {
@@ -376,8 +377,10 @@ struct GemmWork {
   __device__ int n_items() const { return L < n_tiles ? (n_tiles - L + G - 1) / G : 0; }
   __device__ WorkItem item(int i) const {
     const int q = i * G + L;
-    const int mt = q % a.n_mt, rest = q / a.n_mt;
-    const int nt = rest % a.n_nt, ks = rest / a.n_nt;
+    const int per_split = a.n_mt * a.n_nt;
+    const int ks = q / per_split;
+    int mt, nt;
+    block_decode(q - ks * per_split, a.n_mt, a.ba, a.bb, mt, nt);
     const int k0 = ks * a.ksteps * GCfg::BK;
     WorkItem it;
     it.A0 = it.A1 = a.A + (int64_t)mt * GCfg::BM * a.lda + k0;
@@ -689,6 +692,8 @@ hipError_t launch_gemm(const GemmDesc& d, int n_cu, hipStream_t st) {
   a.out_f32 = d.out_f32; a.accumulate = d.accumulate;
   a.n_mt = (d.M + GCfg::BM - 1) / GCfg::BM;
   a.n_nt = (d.N + BN - 1) / BN;
+  a.ba = largest_divisor_le(a.n_mt, 8);
+  a.bb = largest_divisor_le(a.n_nt, 4);
   const int tiles = a.n_mt * a.n_nt * a.n_ksplit;
   const int grid = tiles < n_cu ? tiles : n_cu;
   return launch_big(gemm_kernel, grid, GCfg::NT, GCfg::SMEM_BYTES, st, &a);
