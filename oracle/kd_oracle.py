@@ -25,6 +25,16 @@ The paper names the divergences without printing formulas.  Readings taken:
   * the loss is the masked mean over tokens: sum_t mask_t l_t / sum_t mask_t,
     and is 0 with zero gradients when every token is masked;
   * 0 log 0 := 0.
+Further divergences of the paper's list (Sec. 3.4 names TVD; Table 1 lists skewed
+forward / reverse KL), with `beta` doubling as the skew weight alpha:
+  * TVD = 1/2 sum_v |p_t - p_s|;
+  * skewed FKL = KL(p_t || alpha p_t + (1-alpha) p_s),
+    skewed RKL = KL(p_s || (1-alpha) p_t + alpha p_s)   (the skew divergences of
+    the DistiLLM paper the authors cite; alpha -> 0 recovers FKL / RKL).
+For every divergence that is a function D(p_s) of the student probabilities, the
+gradient through the softmax is g = p_s * (c - sum_v p_s c) with c = dD/dp_s:
+  TVD: c = 1/2 sign(p_s - p_t);   skewed FKL: c = -(1-alpha) p_t / M;
+  skewed RKL: c = (log p_s - log M) + 1 - alpha p_s / M.
 Every function below is pinned by tests that do not call it to make their
 expected values (closed forms, library routines for special cases, finite
 differences, inequalities); see tests/test_oracle_pins.py.
@@ -40,8 +50,8 @@ from __future__ import annotations
 
 import numpy as np
 
-FKL, RKL, JSD = 0, 1, 2
-KIND_NAMES = {FKL: "fkl", RKL: "rkl", JSD: "jsd"}
+FKL, RKL, JSD, TVD, SKEW_FKL, SKEW_RKL = 0, 1, 2, 3, 4, 5
+KIND_NAMES = {FKL: "fkl", RKL: "rkl", JSD: "jsd", TVD: "tvd", SKEW_FKL: "skew_fkl", SKEW_RKL: "skew_rkl"}
 
 # storage order of an output head: W_HV is the mathematical [H, V] array,
 # W_VH is its transpose [V, H] (the order lm_head.weight is kept in).
@@ -101,6 +111,24 @@ def divergence_rows(z_t, z_s, tau, kind, beta=0.5):
         k_t = _xlogy_diff(pt, lt, lm)          # KL(p_t || M)
         l = beta * k_t + (1.0 - beta) * k_s
         g = (1.0 - beta) * ps * ((ls - lm) - k_s[:, None])
+    elif kind == TVD:
+        d = ps - pt
+        l = 0.5 * np.abs(d).sum(axis=-1)
+        c = 0.5 * np.sign(d)
+        g = ps * (c - (ps * c).sum(axis=-1, keepdims=True))
+    elif kind in (SKEW_FKL, SKEW_RKL):
+        alpha = beta
+        if not (0.0 < alpha < 1.0):
+            raise ValueError("skewed KL needs 0 < alpha < 1")
+        if kind == SKEW_FKL:
+            lm = np.logaddexp(np.log(alpha) + lt, np.log1p(-alpha) + ls)   # M = a pt + (1-a) ps
+            l = _xlogy_diff(pt, lt, lm)
+            c = -(1.0 - alpha) * np.exp(lt - lm)
+        else:
+            lm = np.logaddexp(np.log1p(-alpha) + lt, np.log(alpha) + ls)   # M = (1-a) pt + a ps
+            l = _xlogy_diff(ps, ls, lm)
+            c = (ls - lm) + 1.0 - alpha * np.exp(ls - lm)
+        g = ps * (c - (ps * c).sum(axis=-1, keepdims=True))
     else:
         raise ValueError("unknown kind")
     return l, g

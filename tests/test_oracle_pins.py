@@ -15,7 +15,8 @@ def _rand_problem(rng, T=5, Ht=7, Hs=4, V=33, wt=0.7, ws=0.5):
                 h_s=rng.standard_normal((T, Hs)), W_s=ws * rng.standard_normal((Hs, V)))
 
 
-KINDS = [(O.FKL, 0.5), (O.RKL, 0.5), (O.JSD, 0.5), (O.JSD, 0.1), (O.JSD, 0.8)]
+KINDS = [(O.FKL, 0.5), (O.RKL, 0.5), (O.JSD, 0.5), (O.JSD, 0.1), (O.JSD, 0.8),
+         (O.TVD, 0.5), (O.SKEW_FKL, 0.1), (O.SKEW_FKL, 0.6), (O.SKEW_RKL, 0.1), (O.SKEW_RKL, 0.6)]
 
 
 # ---- 1. teacher == student -> 0 and zero gradient ---------------------------------------
@@ -41,6 +42,35 @@ def test_bounds(kind, beta, tau):
         assert (l <= bound + 1e-12).all() and bound <= np.log(2) + 1e-15
     # softmax tangent space: every gradient row sums to zero
     assert np.abs(g.sum(axis=1)).max() < 1e-12
+
+
+def test_tvd_and_skewed_kl_against_library_routines():
+    from scipy.spatial.distance import cityblock
+    rng = np.random.default_rng(21)
+    z_t = 2 * rng.standard_normal((6, 40)); z_s = rng.standard_normal((6, 40)); tau = 1.5
+    pt = sps.softmax(z_t / tau, axis=1); ps = sps.softmax(z_s / tau, axis=1)
+    tv, _ = O.divergence_rows(z_t, z_s, tau, O.TVD)
+    fkl, _ = O.divergence_rows(z_t, z_s, tau, O.FKL)
+    for i in range(6):
+        assert abs(tv[i] - 0.5 * cityblock(pt[i], ps[i])) < 1e-14
+        assert 0 <= tv[i] <= 1 and tv[i] <= np.sqrt(fkl[i] / 2) + 1e-12        # Pinsker
+    for a in (0.1, 0.6):
+        sf, _ = O.divergence_rows(z_t, z_s, tau, O.SKEW_FKL, a)
+        sr, _ = O.divergence_rows(z_t, z_s, tau, O.SKEW_RKL, a)
+        for i in range(6):
+            assert abs(sf[i] - sst.entropy(pt[i], a * pt[i] + (1 - a) * ps[i])) < 1e-13
+            assert abs(sr[i] - sst.entropy(ps[i], (1 - a) * pt[i] + a * ps[i])) < 1e-13
+    # alpha -> 0 recovers the plain divergences; the skew always shrinks them
+    rkl, _ = O.divergence_rows(z_t, z_s, tau, O.RKL)
+    sf, _ = O.divergence_rows(z_t, z_s, tau, O.SKEW_FKL, 1e-9)
+    sr, _ = O.divergence_rows(z_t, z_s, tau, O.SKEW_RKL, 1e-9)
+    assert np.allclose(sf, fkl, rtol=1e-6) and np.allclose(sr, rkl, rtol=1e-6)
+    sf, _ = O.divergence_rows(z_t, z_s, tau, O.SKEW_FKL, 0.3)
+    assert (sf < fkl).all()
+    # disjoint supports: TVD = 1
+    a = np.array([[300.0, 0.0, -300.0, -300.0]]); b = np.array([[-300.0, -300.0, 0.0, 300.0]])
+    tv, _ = O.divergence_rows(a, b, 1.0, O.TVD)
+    assert abs(tv[0] - 1.0) < 1e-12
 
 
 def test_jsd_reaches_its_bound_for_disjoint_supports():
@@ -109,7 +139,8 @@ def test_high_temperature_decay():
     for kind, beta in KINDS:
         l1, _ = O.divergence_rows(z_t, z_s, 100.0, kind, beta)
         l2, _ = O.divergence_rows(z_t, z_s, 200.0, kind, beta)
-        assert np.allclose(l1 / l2, 4.0, rtol=2e-2)      # O(1/tau^2)
+        want = 2.0 if kind == O.TVD else 4.0             # KL-type: O(1/tau^2); TVD is a norm: O(1/tau)
+        assert np.allclose(l1 / l2, want, rtol=2e-2)
 
 
 def test_jsd_role_swap_and_small_beta_limit():
