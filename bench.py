@@ -108,8 +108,8 @@ def main():
     fam = {}
     n_chunks = (V + vc - 1) // vc
     for name, which in (("grad", K.PROF_GRAD), ("gemm_grad_W", K.PROF_GEMM_GRAD_W),
-                        ("gemm_grad_h", K.PROF_GEMM_GRAD_H), ("jsd_rows", K.PROF_JSD_ROWS)):
-        if which == K.PROF_JSD_ROWS and cfg.kind != I.JSD:
+                        ("gemm_grad_h", K.PROF_GEMM_GRAD_H), ("rows", K.PROF_ROWS)):
+        if which == K.PROF_ROWS and cfg.kind < I.JSD:
             continue
         t = K.KernelTimer(which, n_chunks + 1)
         with t:
@@ -119,7 +119,7 @@ def main():
 
     n_valid = int(data["mask"].sum())
     logit_flop = 2.0 * T * V * (H_t + H_s)                 # one pass over every logit, both heads
-    passes = 3 if cfg.kind == I.JSD else 2
+    passes = 3 if cfg.kind >= I.JSD else 2
     flop_alg = T * V * (2.0 * H_t + 6.0 * H_s)
     flop_exec = passes * logit_flop + 4.0 * T * V * H_s
     stats_tflops = logit_flop / (stats_avg * 1e-3) / 1e12
@@ -137,7 +137,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "T": T, "H_t": H_t, "H_s": H_s, "V": V,
-                   "kind": {0: "fkl", 1: "rkl", 2: "jsd"}[cfg.kind], "tau": cfg.tau, "beta": cfg.beta,
+                   "kind": {0: "fkl", 1: "rkl", 2: "jsd", 3: "tvd", 4: "skew_fkl", 5: "skew_rkl"}[cfg.kind], "tau": cfg.tau, "beta": cfg.beta,
                    "valid_tokens": n_valid, "w_layout": "VH", "vocab_chunk": vc, "launches_per_step": n_launch},
         "roofline": {"bound": "mfma", "kernel": "stats_kernel", "achieved": stats_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": stats_tflops / PEAK_BF16_TFLOPS,

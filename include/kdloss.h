@@ -18,7 +18,8 @@
  *   n = sum_t mask_t,  loss = sum_t mask_t l_t / n   (0 when n == 0)
  *   grad_h_s = dL/dz_s . W_s^T,   grad_W_s = h_s^T . dL/dz_s
  * No tau^2 factor is applied.  Logits are never stored: they are produced
- * vocabulary tile by vocabulary tile in registers, twice (three times for JSD).
+ * vocabulary tile by vocabulary tile in registers, twice (three times for JSD,
+ * TVD and the skewed KLs, whose row value needs both log-sum-exps first).
  *
  * Conventions of every entry point
  *  - plain C ABI; no exceptions, no global state, no allocation, no device
@@ -43,14 +44,17 @@ typedef enum {
   KD_ERR_NULL = 1,        /* a required pointer is NULL                          */
   KD_ERR_SHAPE = 2,       /* T, H_t, H_s or V < 1, or beyond the supported range */
   KD_ERR_ALIGN = 3,       /* pointer not 16-byte aligned, or H_t/H_s/V % 8 != 0  */
-  KD_ERR_PARAM = 4,       /* tau <= 0 or not finite, unknown enum, beta outside (0,1) for JSD */
+  KD_ERR_PARAM = 4,       /* tau <= 0 or not finite, unknown enum, beta outside (0,1) where it is used */
   KD_ERR_WORKSPACE = 5,   /* workspace_bytes smaller than kd_loss_workspace_size */
   KD_ERR_UNSUPPORTED = 6, /* valid request this build does not implement         */
   KD_ERR_LAUNCH = 7       /* the HIP runtime refused a launch (see hipGetLastError) */
 } kd_status;
 
-/* Sec. 3.4: built-in divergence metrics */
-typedef enum { KD_FKL = 0, KD_RKL = 1, KD_JSD = 2 } kd_kind;
+/* Sec. 3.4 / Table 1: built-in divergence metrics.
+ *   KD_TVD      = 1/2 sum_v |p_t - p_s|
+ *   KD_SKEW_FKL = KL(p_t || a p_t + (1-a) p_s),  KD_SKEW_RKL = KL(p_s || (1-a) p_t + a p_s),
+ *   with the skew weight a passed in `beta` (0 < a < 1; a -> 0 recovers FKL / RKL). */
+typedef enum { KD_FKL = 0, KD_RKL = 1, KD_JSD = 2, KD_TVD = 3, KD_SKEW_FKL = 4, KD_SKEW_RKL = 5 } kd_kind;
 
 typedef enum { KD_BF16 = 0, KD_F32 = 1 } kd_dtype;
 
@@ -69,8 +73,8 @@ typedef struct {
   int32_t w_layout;     /* kd_wlayout                                               */
   int32_t kind;         /* kd_kind                                                  */
   float tau;            /* temperature, > 0                                         */
-  float beta;           /* JSD mixing weight on the teacher term, 0 < beta < 1;
-                           ignored for FKL / RKL                                    */
+  float beta;           /* JSD mixing weight on the teacher term, or the skew weight
+                           of the skewed KLs; 0 < beta < 1; ignored for FKL/RKL/TVD */
   int32_t accumulate_grad_W; /* 0: grad_W_s is overwritten. 1: added to (gradient
                            accumulation over micro-batches, Table 3 caption)        */
   int32_t reserved;     /* must be 0                                                */
@@ -138,7 +142,7 @@ kd_status kd_loss_plan_info(const kd_loss_params* params, int64_t* vocab_chunk,
  * hook.  which < 0 clears the hook.  Host only; touches no device memory. */
 typedef enum {
   KD_PROF_STATS = 0,        /* logit tiles + online log-sum-exp (one launch per call)   */
-  KD_PROF_JSD_ROWS = 1,     /* JSD row pass (one launch per call, JSD only)             */
+  KD_PROF_ROWS = 1,         /* row pass of JSD / TVD / skewed KL (one launch per call)  */
   KD_PROF_GRAD = 2,         /* logit tiles + dL/dz_s epilogue (one launch per chunk)    */
   KD_PROF_GEMM_GRAD_W = 3,  /* grad_W_s product (one launch per chunk)                  */
   KD_PROF_GEMM_GRAD_H = 4   /* grad_h_s product (one launch per chunk)                  */

@@ -26,9 +26,11 @@ kd_status check_params(const kd_loss_params* p) {
   if (p->in_dtype != KD_BF16 && p->in_dtype != KD_F32) return KD_ERR_PARAM;
   if (p->grad_dtype != KD_BF16 && p->grad_dtype != KD_F32) return KD_ERR_PARAM;
   if (p->w_layout != KD_W_HV && p->w_layout != KD_W_VH) return KD_ERR_PARAM;
-  if (p->kind != KD_FKL && p->kind != KD_RKL && p->kind != KD_JSD) return KD_ERR_PARAM;
+  if (p->kind < KD_FKL || p->kind > KD_SKEW_RKL) return KD_ERR_PARAM;
   if (!(p->tau > 0.f) || !std::isfinite(p->tau)) return KD_ERR_PARAM;
-  if (p->kind == KD_JSD && !(p->beta > 0.f && p->beta < 1.f)) return KD_ERR_PARAM;
+  if ((p->kind == KD_JSD || p->kind == KD_SKEW_FKL || p->kind == KD_SKEW_RKL) &&
+      !(p->beta > 0.f && p->beta < 1.f))
+    return KD_ERR_PARAM;
   if (p->accumulate_grad_W != 0 && p->accumulate_grad_W != 1) return KD_ERR_PARAM;
   if (p->reserved != 0) return KD_ERR_PARAM;
   if (p->w_layout != KD_W_VH) return KD_ERR_UNSUPPORTED;
@@ -181,12 +183,12 @@ kd_status run_forward(const Problem& q, hipStream_t st) {
     KD_TRY(kd::launch_stats(q, st));
   }
   KD_TRY(kd::launch_combine(q, st));
-  if (q.kind == KD_JSD) {
+  if (q.kind >= KD_JSD) {   // divergences that need both log-sum-exps before their row value
     {
-      ProfileScope ps(KD_PROF_JSD_ROWS, st);
-      KD_TRY(kd::launch_jsd_rows(q, st));
+      ProfileScope ps(KD_PROF_ROWS, st);
+      KD_TRY(kd::launch_rows(q, st));
     }
-    KD_TRY(kd::launch_combine_jsd(q, st));
+    KD_TRY(kd::launch_combine_rows(q, st));
   }
   KD_TRY(kd::launch_finalize(q, st));
   return KD_OK;
@@ -235,7 +237,7 @@ kd_status kd_loss_plan_info(const kd_loss_params* params, int64_t* vocab_chunk, 
   plan(params, q, L, true);
   const int64_t chunks = (q.V + q.V_c - 1) / q.V_c;
   if (vocab_chunk) *vocab_chunk = q.V_c;
-  if (n_launches) *n_launches = 3 + (q.kind == KD_JSD ? 2 : 0) + 1 + chunks * 4 + 1;
+  if (n_launches) *n_launches = 3 + (q.kind >= KD_JSD ? 2 : 0) + 1 + chunks * 4 + 1;
   return KD_OK;
 }
 

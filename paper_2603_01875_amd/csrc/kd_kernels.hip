@@ -3,7 +3,7 @@
 // Pass structure (one call of kd_loss_fwd_bwd):
 //   stats    : logit tiles (student then teacher) -> online max / sum-exp / cross term per token
 //   combine  : merge partial statistics -> log-sum-exps, FKL / RKL row losses
-//   jsd_rows : (JSD only) logit tiles again -> KL(p_t||M), KL(p_s||M) per token
+//   rows     : (JSD, TVD, skewed KL) logit tiles again -> two row sums per token (RowTerm)
 //   finalize : n = sum mask, loss, per-row gradient scale mask/(n tau)
 //   per vocabulary chunk:
 //     grad   : logit tiles again -> dL/dz_s tile in bf16, stored both [T,Vc] and [Vc,T]
@@ -208,13 +208,57 @@ struct StatsEpi {
   }
 };
 
-// JSD row sums with both log-sum-exps known:  A1 = sum p_t (l_t - l_m),  A2 = sum p_s (l_s - l_m)
-// (base-2 logs), M = beta p_t + (1 - beta) p_s.
-struct JsdEpi {
+// Divergences whose row value needs both log-sum-exps first (JSD, TVD, skewed KL) share one
+// scheme.  With D a function of the student probabilities and c = dD/dp_s, the gradient through the
+// softmax is  dD/dz_s = p_s (c - R) / tau,  R = sum_v p_s c.  A row pass over the logit tiles
+// accumulates two sums (a1, a2) per token, from which the row loss and R follow; the gradient pass
+// evaluates c element by element.  lt, ls are base-2 log-probabilities, w is beta (JSD) or the skew
+// weight alpha.
+//   JSD       M = w p_t + (1-w) p_s    a1 = sum p_t (lt - lm)   a2 = sum p_s (ls - lm)
+//             loss = ln2 (w a1 + (1-w) a2)     c = (1-w) ln2 (ls - lm)          R = (1-w) ln2 a2
+//   TVD       d = p_s - p_t            a1 = sum |d|             a2 = sum p_s sign(d)
+//             loss = a1 / 2                    c = sign(d) / 2                  R = a2 / 2
+//   skew FKL  M = w p_t + (1-w) p_s    a1 = sum p_t (lt - lm)   a2 = sum p_s p_t / M
+//             loss = ln2 a1                    c = -(1-w) p_t / M               R = -(1-w) a2
+//   skew RKL  M = (1-w) p_t + w p_s    a1 = sum p_s (ls - lm)   a2 = sum p_s c
+//             loss = ln2 a1                    c = ln2 (ls - lm) + 1 - w p_s / M   R = a2
+template <int KIND>
+struct RowTerm {
+  // c for one element; also adds the element's contribution to (a1, a2) when ACC is set
+  template <bool ACC>
+  static __device__ __forceinline__ float eval(float lt, float ls, float w, float& a1, float& a2) {
+    const float pt = fexp2(lt), ps = fexp2(ls);
+    if (KIND == 3) {
+      const float d = ps - pt;
+      const float sg = (d > 0.f ? 1.f : 0.f) - (d < 0.f ? 1.f : 0.f);
+      if (ACC) { a1 += fabsf(d); a2 = fmaf(ps, sg, a2); }
+      return 0.5f * sg;
+    }
+    const float wt = (KIND == 5) ? 1.f - w : w;          // weight of p_t in the mixture
+    const float M = fmaf(wt, pt, (1.f - wt) * ps);
+    const float lm = M > 0.f ? flog2(M) : 0.f;           // M == 0 only where p_t = p_s = 0
+    if (KIND == 2) {
+      if (ACC) { a1 = fmaf(pt, lt - lm, a1); a2 = fmaf(ps, ls - lm, a2); }
+      return (1.f - w) * LN2 * (ls - lm);
+    }
+    if (KIND == 4) {
+      const float r = M > 0.f ? fexp2(lt - lm) : 0.f;    // p_t / M
+      if (ACC) { a1 = fmaf(pt, lt - lm, a1); a2 = fmaf(ps, r, a2); }
+      return -(1.f - w) * r;
+    }
+    const float r = M > 0.f ? fexp2(ls - lm) : 0.f;      // p_s / M
+    const float cc = fmaf(LN2, ls - lm, 1.f - w * r);
+    if (ACC) { a1 = fmaf(ps, ls - lm, a1); a2 = fmaf(ps, cc, a2); }
+    return cc;
+  }
+};
+
+template <int KIND>
+struct RowsEpi {
   float A1[NI], A2[NI], Lt[NI], Ls[NI];
-  float c, beta;
+  float c, w;
   int wm, wn, lane;
-  __device__ JsdEpi(const LogitArgs& a, int tt) : c(a.c), beta(a.beta) {
+  __device__ RowsEpi(const LogitArgs& a, int tt) : c(a.c), w(a.beta) {
     lane = threadIdx.x & 63;
     wm = (threadIdx.x >> 6) & 1;
     wn = threadIdx.x >> 7;
@@ -227,7 +271,6 @@ struct JsdEpi {
   __device__ void begin_item(const WorkItem&) {}
   __device__ void end_item(const WorkItem& it, AccTile& accS, AccTile& accT) {
     mask_tail_rows(it, accS, accT, wm, lane);
-    const float omb = 1.f - beta;
 #pragma unroll
     for (int nt = 0; nt < NI; ++nt) {
       float a1 = A1[nt], a2 = A2[nt];
@@ -237,11 +280,7 @@ struct JsdEpi {
         for (int r = 0; r < 16; ++r) {
           const float lt = fmaf(accT[mt][nt][r], c, -Lt[nt]);
           const float ls = fmaf(accS[mt][nt][r], c, -Ls[nt]);
-          const float pt = fexp2(lt), ps = fexp2(ls);
-          const float M = fmaf(beta, pt, omb * ps);
-          const float lm = M > 0.f ? flog2(M) : 0.f;
-          a1 = fmaf(pt, lt - lm, a1);
-          a2 = fmaf(ps, ls - lm, a2);
+          (void)RowTerm<KIND>::template eval<true>(lt, ls, w, a1, a2);
         }
       A1[nt] = a1; A2[nt] = a2;
     }
@@ -260,8 +299,8 @@ struct JsdEpi {
 
 // dL/dz_s tile.  rowinfo = {lse2_t, lse2_s, s = mask/(n tau), R}
 //   FKL: dz = s (p_s - p_t)
-//   RKL: dz = s p_s (ln2 (l_s - l_t) - R),           R = row loss
-//   JSD: dz = s (1-beta) p_s (ln2 (l_s - l_m) - R),  R = KL(p_s || M)
+//   RKL: dz = s p_s (ln2 (l_s - l_t) - R),   R = row loss
+//   JSD, TVD, skewed KL: dz = s p_s (c - R)  (RowTerm above)
 template <int KIND>
 struct GradEpi {
   const LogitArgs& a;
@@ -280,12 +319,12 @@ struct GradEpi {
     }
   }
   __device__ void end_item(const WorkItem& it, AccTile& accS, AccTile& accT) {
-    const float c = a.c, beta = a.beta, omb = 1.f - a.beta;
+    const float c = a.c, w = a.beta;
     const int mloc0 = it.m0 - a.vt0 * BM;      // vocabulary offset inside the chunk
 #pragma unroll
     for (int nt = 0; nt < NI; ++nt) {
       const int n = it.n0 + acc_n(wn, nt, lane);
-      const float s = KIND == 2 ? sc[nt] * omb : sc[nt];
+      const float s = sc[nt];
 #pragma unroll
       for (int mt = 0; mt < MI; ++mt)
 #pragma unroll
@@ -304,9 +343,8 @@ struct GradEpi {
             } else if (KIND == 1) {
               g = ps * fmaf(LN2, ls - lt, -R[nt]);
             } else {
-              const float M = fmaf(beta, fexp2(lt), omb * ps);
-              const float lm = M > 0.f ? flog2(M) : 0.f;
-              g = ps * fmaf(LN2, ls - lm, -R[nt]);
+              float u1, u2;
+              g = ps * (RowTerm<KIND>::template eval<false>(lt, ls, w, u1, u2) - R[nt]);
             }
             const float d = ok ? s * g : 0.f;
             o[i] = (bf16_t)d;
@@ -333,10 +371,11 @@ KD_LOGIT_KERNEL void stats_kernel(const LogitArgs a) {
   epi.write(a, work.tt, work.split);
 }
 
-KD_LOGIT_KERNEL void jsd_rows_kernel(const LogitArgs a) {
+template <int KIND>
+KD_LOGIT_KERNEL void rows_kernel(const LogitArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   SplitWork work(a);
-  JsdEpi epi(a, work.tt);
+  RowsEpi<KIND> epi(a, work.tt);
   tile_loop<2, LCfg>(work, epi, a.H_s, a.H_t, a.H_s, a.H_t, smem);
   epi.write(a, work.tt, work.split);
 }
@@ -475,15 +514,15 @@ __global__ void combine_kernel(const float* partials, int n_parts, int T, int T_
   }
   const float Lt = Mt + flog2(St), Ls = Ms + flog2(Ss);
   float loss = 0.f;
-  if (kind == 0) loss = LN2 * (c * X / St - Lt + Ls);
+  if (kind == 0) loss = LN2 * (c * X / St - Lt + Ls);   // kinds >= 2: filled in by combine_rows_kernel
   if (kind == 1) loss = LN2 * (c * X / Ss - Ls + Lt);
   rowinfo[t] = f32x4{Lt, Ls, 0.f, loss};
   row_loss[t] = loss;
 }
 
-// JSD: merge the row sums.  row loss = ln2 (beta A1 + (1-beta) A2),  R = KL(p_s||M) = ln2 A2
-__global__ void combine_jsd_kernel(const float* partials, int n_parts, int T, int T_pad, float beta,
-                                   f32x4* rowinfo, float* row_loss) {
+// JSD / TVD / skewed KL: merge the row sums into the row loss and R (see RowTerm).
+__global__ void combine_rows_kernel(const float* partials, int n_parts, int T, int T_pad, int kind, float w,
+                                    f32x4* rowinfo, float* row_loss) {
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= T) return;
   float A1 = 0.f, A2 = 0.f;
@@ -492,10 +531,15 @@ __global__ void combine_jsd_kernel(const float* partials, int n_parts, int T, in
     A1 += q[0];
     A2 += q[T_pad];
   }
+  float loss, R;
+  if (kind == 2) { loss = LN2 * (w * A1 + (1.f - w) * A2); R = (1.f - w) * LN2 * A2; }
+  else if (kind == 3) { loss = 0.5f * A1; R = 0.5f * A2; }
+  else if (kind == 4) { loss = LN2 * A1; R = -(1.f - w) * A2; }
+  else { loss = LN2 * A1; R = A2; }
   f32x4 ri = rowinfo[t];
-  ri[3] = LN2 * A2;
+  ri[3] = R;
   rowinfo[t] = ri;
-  row_loss[t] = LN2 * (beta * A1 + (1.f - beta) * A2);
+  row_loss[t] = loss;
 }
 
 // One workgroup: n = sum mask, loss = sum mask l / n, per-row gradient scale mask / (n tau).
@@ -624,17 +668,23 @@ hipError_t launch_stats(const Problem& p, hipStream_t st) {
   switch (p.kind) {
     case 0: return launch_big(stats_kernel<0>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
     case 1: return launch_big(stats_kernel<1>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
-    default: return launch_big(stats_kernel<2>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
+    default: return launch_big(stats_kernel<2>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);   // log-sum-exps only
   }
 }
 
-hipError_t launch_jsd_rows(const Problem& p, hipStream_t st) {
+hipError_t launch_rows(const Problem& p, hipStream_t st) {
   LogitArgs a = make_logit_args(p);
   a.vt0 = 0; a.n_vt = p.n_vt; a.n_split = p.n_split;
   a.ba = largest_divisor_le(p.n_tt, 4);
   a.bb = largest_divisor_le(p.n_split, 8);
   a.partials = p.partials;
-  return launch_big(jsd_rows_kernel, p.n_tt * p.n_split, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
+  const int grid = p.n_tt * p.n_split;
+  switch (p.kind) {
+    case 2: return launch_big(rows_kernel<2>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
+    case 3: return launch_big(rows_kernel<3>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
+    case 4: return launch_big(rows_kernel<4>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
+    default: return launch_big(rows_kernel<5>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
+  }
 }
 
 hipError_t launch_combine(const Problem& p, hipStream_t st) {
@@ -644,10 +694,10 @@ hipError_t launch_combine(const Problem& p, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t launch_combine_jsd(const Problem& p, hipStream_t st) {
+hipError_t launch_combine_rows(const Problem& p, hipStream_t st) {
   const int n_parts = p.n_split * 4;
-  hipLaunchKernelGGL(combine_jsd_kernel, dim3((p.T + 255) / 256), dim3(256), 0, st, p.partials, n_parts, p.T,
-                     p.T_pad, p.beta, (f32x4*)p.rowinfo, p.row_loss);
+  hipLaunchKernelGGL(combine_rows_kernel, dim3((p.T + 255) / 256), dim3(256), 0, st, p.partials, n_parts, p.T,
+                     p.T_pad, p.kind, p.beta, (f32x4*)p.rowinfo, p.row_loss);
   return hipGetLastError();
 }
 
@@ -669,7 +719,10 @@ hipError_t launch_grad_chunk(const Problem& p, int v0, int width, hipStream_t st
   switch (p.kind) {
     case 0: return launch_big(grad_kernel<0>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
     case 1: return launch_big(grad_kernel<1>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
-    default: return launch_big(grad_kernel<2>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
+    case 2: return launch_big(grad_kernel<2>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
+    case 3: return launch_big(grad_kernel<3>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
+    case 4: return launch_big(grad_kernel<4>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
+    default: return launch_big(grad_kernel<5>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
   }
 }
 

@@ -10,7 +10,7 @@ from __future__ import annotations
 import ctypes
 import os
 
-FKL, RKL, JSD = 0, 1, 2
+FKL, RKL, JSD, TVD, SKEW_FKL, SKEW_RKL = 0, 1, 2, 3, 4, 5
 BF16, F32 = 0, 1
 W_HV, W_VH = 0, 1
 
@@ -89,7 +89,7 @@ def kd_loss_plan_info(params: KdLossParams):
     return int(vc.value), int(nl.value)
 
 
-PROF_STATS, PROF_JSD_ROWS, PROF_GRAD, PROF_GEMM_GRAD_W, PROF_GEMM_GRAD_H = range(5)
+PROF_STATS, PROF_ROWS, PROF_GRAD, PROF_GEMM_GRAD_W, PROF_GEMM_GRAD_H = range(5)
 
 
 class KernelTimer:

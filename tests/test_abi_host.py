@@ -58,7 +58,8 @@ def test_workspace_is_far_below_T_times_V():
 @pytest.mark.parametrize("kw,status", [
     (dict(T=0), 2), (dict(V=-8), 2), (dict(H_t=100), 3), (dict(V=151937), 3),
     (dict(tau=0.0), 4), (dict(tau=float("nan")), 4), (dict(kind=7), 4),
-    (dict(kind=K.JSD, beta=0.0), 4), (dict(kind=K.JSD, beta=1.0), 4), (dict(in_dtype=5), 4),
+    (dict(kind=K.JSD, beta=0.0), 4), (dict(kind=K.JSD, beta=1.0), 4), (dict(kind=K.SKEW_FKL, beta=0.0), 4),
+    (dict(kind=K.SKEW_RKL, beta=1.5), 4), (dict(kind=-1), 4), (dict(in_dtype=5), 4),
     (dict(w_layout=K.W_HV), 6),
 ])
 def test_bad_params_are_rejected(kw, status):
@@ -76,6 +77,7 @@ def test_fp32_and_odd_hidden_sizes_need_more_workspace():
 
 def test_beta_ignored_for_kl():
     K.kd_loss_workspace_size(_ws(kind=K.FKL, beta=5.0))
+    K.kd_loss_workspace_size(_ws(kind=K.TVD, beta=-1.0))
 
 
 def test_pointer_checks_run_before_any_gpu_work():

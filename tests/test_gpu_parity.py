@@ -124,3 +124,19 @@ def test_fp32_inputs_other_kinds():
         cfg = I.scaled(I.workload(name), batch=2, seq=100, H_t=96, H_s=40, V=520, dtype=I.F32)
         data = I.generate(cfg)
         G.check(G.run_gpu(cfg, data), G.run_oracle(cfg, data), f"fp32 {name}")
+
+
+@pytest.mark.parametrize("kind,w", [(I.TVD, 0.5), (I.SKEW_FKL, 0.1), (I.SKEW_RKL, 0.1), (I.SKEW_FKL, 0.7)])
+@pytest.mark.parametrize("name", ["fkl_bf16", "rkl_bf16"])       # mild and sharper teacher
+def test_tvd_and_skewed_kl(name, kind, w, monkeypatch):
+    monkeypatch.setenv("KD_VOCAB_CHUNK", "1024")
+    cfg = I.scaled(I.workload(name), batch=2, seq=200, H_t=192, H_s=128, V=2440, kind=kind, beta=w, tau=1.3)
+    data = I.generate(cfg)
+    extra = G.tvd_tie_allowance(cfg, data) if kind == I.TVD else None      # near-ties: either sign is valid
+    G.check(G.run_gpu(cfg, data), G.run_oracle(cfg, data), f"{name} kind={kind} w={w}", extra)
+
+
+def test_tvd_peaked_teacher():
+    cfg = I.scaled(I.workload("long_peaked"), batch=1, seq=256, H_t=1024, H_s=256, V=4096, kind=I.TVD)
+    data = I.generate(cfg)
+    G.check(G.run_gpu(cfg, data), G.run_oracle(cfg, data), "tvd peaked", G.tvd_tie_allowance(cfg, data))
