@@ -118,10 +118,13 @@ def main():
         fam[name] = sum(t.durations_ms())
 
     n_valid = int(data["mask"].sum())
-    logit_flop = 2.0 * T * V * (H_t + H_s)                 # one pass over every logit, both heads
+    # masked tokens are compacted away on the device: the kernels work on the valid tokens, rounded up
+    # to whole 256-token tiles; flop figures count exactly those rows
+    T_comp = (n_valid + 255) // 256 * 256
+    logit_flop = 2.0 * T_comp * V * (H_t + H_s)            # one pass over every computed logit, both heads
     passes = 3 if cfg.kind >= I.JSD else 2
-    flop_alg = T * V * (2.0 * H_t + 6.0 * H_s)
-    flop_exec = passes * logit_flop + 4.0 * T * V * H_s
+    flop_alg = n_valid * V * (2.0 * H_t + 6.0 * H_s)
+    flop_exec = passes * logit_flop + 4.0 * T_comp * V * H_s
     stats_tflops = logit_flop / (stats_avg * 1e-3) / 1e12
 
     traffic = None
@@ -138,7 +141,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "T": T, "H_t": H_t, "H_s": H_s, "V": V,
                    "kind": {0: "fkl", 1: "rkl", 2: "jsd", 3: "tvd", 4: "skew_fkl", 5: "skew_rkl"}[cfg.kind], "tau": cfg.tau, "beta": cfg.beta,
-                   "valid_tokens": n_valid, "w_layout": "VH", "vocab_chunk": vc, "launches_per_step": n_launch},
+                   "valid_tokens": n_valid, "computed_token_rows": T_comp, "w_layout": "VH", "vocab_chunk": vc, "launches_per_step": n_launch},
         "roofline": {"bound": "mfma", "kernel": "stats_kernel", "achieved": stats_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": stats_tflops / PEAK_BF16_TFLOPS,
                      "traffic": traffic, "launch_ms": stats_avg, "flop_per_launch": logit_flop},

@@ -17,7 +17,8 @@
  *   JSD: l_t = beta KL(p_t || M) + (1-beta) KL(p_s || M),  M = beta p_t + (1-beta) p_s
  *   n = sum_t mask_t,  loss = sum_t mask_t l_t / n   (0 when n == 0)
  *   grad_h_s = dL/dz_s . W_s^T,   grad_W_s = h_s^T . dL/dz_s
- * No tau^2 factor is applied.  Logits are never stored: they are produced
+ * No tau^2 factor is applied.  Masked tokens are compacted away on the device before any
+ * product is formed, so they cost nothing.  Logits are never stored: they are produced
  * vocabulary tile by vocabulary tile in registers, twice (three times for JSD,
  * TVD and the skewed KLs, whose row value needs both log-sum-exps first).
  *
@@ -96,7 +97,7 @@ kd_status kd_loss_workspace_size(const kd_loss_params* params, size_t* bytes);
  *  W_s  head of the student, device, read-only
  *  mask [T] uint8 device, non-zero = token counts; NULL = every token counts
  *  loss            device, one float: the masked-mean divergence
- *  per_token_loss  device, [T] floats (l_t for every token, masked or not) or NULL
+ *  per_token_loss  device, [T] floats (l_t; 0 for masked tokens, which are never computed) or NULL
  *  grad_h_s [T, H_s] device, grad_dtype; rows of masked tokens are exactly 0
  *  grad_W_s device, grad_dtype, same order as W_s; overwritten or accumulated
  *  workspace       device, 256-byte aligned, workspace_bytes >= the size query

@@ -14,7 +14,7 @@ inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 struct Layout {
-  size_t rowinfo, row_loss, partials, h_sT, W_sT, dz, dzT, gh32, total;
+  size_t meta, rowmap, inv, rowinfo, row_loss, partials, h_sT, W_sT, dz, dzT, gh32, total;
   size_t prep_h_t, prep_W_t, prep_h_s, prep_W_s;   // re-packed operands (only when needed)
 };
 
@@ -50,15 +50,21 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward) {
   q.in_f32 = p->in_dtype == KD_F32;
   q.K_t = (int)round_up(q.in_f32 ? 3 * q.H_t : q.H_t, 64);
   q.K_s = (int)round_up(q.in_f32 ? 3 * q.H_s : q.H_s, 64);
-  q.prep_t = q.in_f32 || q.K_t != q.H_t;
-  q.prep_s = q.in_f32 || q.K_s != q.H_s;
+  q.prep_Wt = q.in_f32 || q.K_t != q.H_t;
+  q.prep_Ws = q.in_f32 || q.K_s != q.H_s;
+  // hidden states are also re-packed when a mask is given: valid tokens are compacted to the front
+  // (the workspace is sized as if it were, since the size query does not see the mask)
+  q.prep_ht = q.prep_hs = 1;
   q.T_pad = (int)round_up(q.T, kd::kTileN);
   q.n_tt = q.T_pad / kd::kTileN;
   q.n_vt = (int)((q.V + kd::kTileM - 1) / kd::kTileM);
-  // vocabulary splits of the statistics passes: enough workgroups to fill the chip, and at least 8
-  // so that the 32 workgroups co-resident on an XCD form a 4 (token) x 8 (vocabulary) block
-  int ns = (q.n_cu + q.n_tt - 1) / q.n_tt;
+  // Vocabulary splits of the statistics passes.  The device picks the actual number once it knows
+  // how many token tiles survive the mask (about n_cu / tiles, at least 8 so that the 32 workgroups
+  // co-resident on an XCD form a 4 x 8 block); this is the upper bound the buffers are sized for:
+  // enough to keep every CU busy with up to half of the tokens masked.
+  int ns = 2 * ((q.n_cu + q.n_tt - 1) / q.n_tt);
   if (ns < 8) ns = 8;
+  if (ns > 32) ns = 32;
   if (ns > q.n_vt) ns = q.n_vt;
   if (ns < 1) ns = 1;
   q.n_split = ns;
@@ -88,18 +94,17 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward) {
 
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = (size_t)round_up((int64_t)(off + bytes), 256); return o; };
+  L.meta = take(64);
+  L.rowmap = take((size_t)q.T_pad * 4);
+  L.inv = take((size_t)q.T * 4);
   L.rowinfo = take((size_t)q.T_pad * 16);
   L.row_loss = take((size_t)q.T_pad * 4);
   L.partials = take((size_t)q.n_split * 4 * 5 * q.T_pad * 4);
   L.prep_h_t = L.prep_W_t = L.prep_h_s = L.prep_W_s = 0;
-  if (q.prep_t) {
-    L.prep_h_t = take((size_t)q.T * q.K_t * 2);
-    L.prep_W_t = take((size_t)q.V * q.K_t * 2);
-  }
-  if (q.prep_s) {
-    L.prep_h_s = take((size_t)q.T * q.K_s * 2);
-    L.prep_W_s = take((size_t)q.V * q.K_s * 2);
-  }
+  if (q.prep_ht) L.prep_h_t = take((size_t)q.T * q.K_t * 2);
+  if (q.prep_Wt) L.prep_W_t = take((size_t)q.V * q.K_t * 2);
+  if (q.prep_hs) L.prep_h_s = take((size_t)q.T * q.K_s * 2);
+  if (q.prep_Ws) L.prep_W_s = take((size_t)q.V * q.K_s * 2);
   if (with_backward) {
     L.h_sT = take((size_t)q.H_s * q.T_pad * 2);
     L.W_sT = take((size_t)q.H_s * q.V_c * 2);
@@ -114,6 +119,9 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward) {
 
 void carve(Problem& q, const Layout& L, void* ws) {
   char* b = static_cast<char*>(ws);
+  q.meta = reinterpret_cast<int*>(b + L.meta);
+  q.rowmap = reinterpret_cast<int*>(b + L.rowmap);
+  q.inv = reinterpret_cast<int*>(b + L.inv);
   q.rowinfo = reinterpret_cast<float*>(b + L.rowinfo);
   q.row_loss = reinterpret_cast<float*>(b + L.row_loss);
   q.partials = reinterpret_cast<float*>(b + L.partials);
@@ -123,8 +131,15 @@ void carve(Problem& q, const Layout& L, void* ws) {
   q.dzT = b + L.dzT;
   q.gh32 = reinterpret_cast<float*>(b + L.gh32);
   q.user_h_t = q.h_t; q.user_W_t = q.W_t; q.user_h_s = q.h_s; q.user_W_s = q.W_s;
-  if (q.prep_t) { q.h_t = b + L.prep_h_t; q.W_t = b + L.prep_W_t; }
-  if (q.prep_s) { q.h_s = b + L.prep_h_s; q.W_s = b + L.prep_W_s; }
+  // without a mask the hidden states are used in place unless they need re-packing anyway
+  if (!q.mask) {
+    q.prep_ht = q.prep_Wt;
+    q.prep_hs = q.prep_Ws;
+  }
+  if (q.prep_ht) q.h_t = b + L.prep_h_t;
+  if (q.prep_Wt) q.W_t = b + L.prep_W_t;
+  if (q.prep_hs) q.h_s = b + L.prep_h_s;
+  if (q.prep_Ws) q.W_s = b + L.prep_W_s;
 }
 
 
@@ -162,18 +177,20 @@ struct ProfileScope {
 
 // Re-pack the operands that need it (fp32 split / K padding) into the workspace.
 kd_status prepare_operands(const Problem& q, hipStream_t st) {
-  if (q.prep_t) {
-    KD_TRY(kd::launch_prepare(q.user_h_t, q.in_f32, q.T, q.H_t, const_cast<void*>(q.h_t), q.K_t, 2, st));
-    KD_TRY(kd::launch_prepare(q.user_W_t, q.in_f32, q.V, q.H_t, const_cast<void*>(q.W_t), q.K_t, 1, st));
-  }
-  if (q.prep_s) {
-    KD_TRY(kd::launch_prepare(q.user_h_s, q.in_f32, q.T, q.H_s, const_cast<void*>(q.h_s), q.K_s, 2, st));
-    KD_TRY(kd::launch_prepare(q.user_W_s, q.in_f32, q.V, q.H_s, const_cast<void*>(q.W_s), q.K_s, 1, st));
-  }
+  const int* map = q.mask ? q.rowmap : nullptr;     // gather valid tokens to the front
+  if (q.prep_ht)
+    KD_TRY(kd::launch_prepare(q.user_h_t, q.in_f32, q.T, q.H_t, const_cast<void*>(q.h_t), q.K_t, 2, map, q.meta, st));
+  if (q.prep_Wt)
+    KD_TRY(kd::launch_prepare(q.user_W_t, q.in_f32, q.V, q.H_t, const_cast<void*>(q.W_t), q.K_t, 1, nullptr, q.meta, st));
+  if (q.prep_hs)
+    KD_TRY(kd::launch_prepare(q.user_h_s, q.in_f32, q.T, q.H_s, const_cast<void*>(q.h_s), q.K_s, 2, map, q.meta, st));
+  if (q.prep_Ws)
+    KD_TRY(kd::launch_prepare(q.user_W_s, q.in_f32, q.V, q.H_s, const_cast<void*>(q.W_s), q.K_s, 1, nullptr, q.meta, st));
   return KD_OK;
 }
 
 kd_status run_forward(const Problem& q, hipStream_t st) {
+  KD_TRY(kd::launch_rowmap(q, st));
   {
     kd_status ps = prepare_operands(q, st);
     if (ps != KD_OK) return ps;
@@ -237,7 +254,7 @@ kd_status kd_loss_plan_info(const kd_loss_params* params, int64_t* vocab_chunk, 
   plan(params, q, L, true);
   const int64_t chunks = (q.V + q.V_c - 1) / q.V_c;
   if (vocab_chunk) *vocab_chunk = q.V_c;
-  if (n_launches) *n_launches = 3 + (q.kind >= KD_JSD ? 2 : 0) + 1 + chunks * 4 + 1;
+  if (n_launches) *n_launches = 6 + (q.kind >= KD_JSD ? 2 : 0) + 1 + chunks * 4 + 1;
   return KD_OK;
 }
 
@@ -286,6 +303,7 @@ kd_status kd_loss_fwd_bwd(const kd_loss_params* params, const void* h_t, const v
     gw.A = q.h_sT; gw.lda = q.T_pad; gw.M = q.H_s;
     gw.B = q.dzT; gw.ldb = q.T_pad; gw.N = width;
     gw.K = q.T_pad; gw.k_per_split = 0;
+    gw.meta = q.meta; gw.k_from_meta = 1;        // only the token tiles that hold valid tokens
     gw.out = static_cast<char*>(q.grad_W_s) + (size_t)v0 * q.H_s * gsz;
     gw.ldo = q.H_s; gw.out_split_stride = 0;
     gw.out_f32 = q.grad_f32; gw.accumulate = q.accumulate_grad_W;
@@ -296,6 +314,7 @@ kd_status kd_loss_fwd_bwd(const kd_loss_params* params, const void* h_t, const v
     kd::GemmDesc gh{};   // grad_h_s[t][h] += sum_v W_sT[h][v] dz[t][v]
     gh.A = q.W_sT; gh.lda = q.V_c; gh.M = q.H_s;
     gh.B = q.dz; gh.ldb = q.V_c; gh.N = q.T;
+    gh.meta = q.meta; gh.n_from_meta = 1;        // rows = valid tokens
     gh.K = (int)round_up(width, 64); gh.k_per_split = q.ksteps_h * 64;
     gh.out = q.gh32; gh.ldo = q.H_s; gh.out_split_stride = (int64_t)q.T * q.H_s;
     gh.out_f32 = 1; gh.accumulate = first ? 0 : 1;

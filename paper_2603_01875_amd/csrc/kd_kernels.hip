@@ -41,8 +41,14 @@ __device__ __forceinline__ int acc_n(int wn, int nt, int lane) { return LCfg::ac
 // Workgroups are dealt to the 8 XCDs round-robin by workgroup id.  Renumber so
 // that consecutive logical ids sit on one XCD (and share its L2).
 __device__ __forceinline__ int xcd_logical_id(int b, int G) {
-  return (G % 8 == 0) ? (b % 8) * (G / 8) + b / 8 : b;
+  const int x = b % 8, q = G / 8, r = G % 8;       // XCD x holds q (+1 if x < r) of the G workgroups
+  return x * q + (x < r ? x : r) + b / 8;
 }
+
+// Device-side plan, written by rowmap_kernel once the mask has been counted (the host never
+// learns how many tokens are valid, so everything that depends on it is decided on the device).
+enum { META_N_VALID = 0, META_N_TT = 1, META_N_SPLIT = 2, META_BA = 3, META_BB = 4, META_T_EFF = 5, META_WORDS = 8 };
+__device__ __forceinline__ int meta_get(const int* meta, int i) { return uniform(meta[i]); }
 
 // Index q over an (na x nb) grid walked in (ba x bb) blocks, a fastest inside a block.
 __device__ __forceinline__ void block_decode(int q, int na, int ba, int bb, int& a, int& b) {
@@ -56,10 +62,9 @@ __device__ __forceinline__ void block_decode(int q, int na, int ba, int bb, int&
 struct LogitArgs {
   const bf16_t* W_s; const bf16_t* h_s; const bf16_t* W_t; const bf16_t* h_t;
   int T, V, H_s, H_t;  // H_*: contraction length and row stride of the (re-packed) operands
-  int n_tt;            // token tiles of BN rows
+  const int* meta;     // device-side plan: valid tokens, token tiles, vocabulary splits, block shape
   int vt0, n_vt;       // vocabulary tiles [vt0, vt0 + n_vt) of BM rows handled by this launch
-  int n_split;         // stats kernels: vocabulary splits (grid = n_tt * n_split)
-  int ba, bb;          // block shape of the work map (ba | n_tt, bb | n_split or n_vt)
+  int bb;              // grad kernel: block width of the work map along the vocabulary (bb | n_vt)
   float c;             // log2(e) / tau
   float beta;
   int T_pad;
@@ -91,10 +96,14 @@ struct SplitWork {
   const LogitArgs& a;
   int tt, split, lo, cnt;
   __device__ SplitWork(const LogitArgs& a_) : a(a_) {
-    const int L = xcd_logical_id(blockIdx.x, gridDim.x);
-    block_decode(L, a.n_tt, a.ba, a.bb, tt, split);
-    lo = (int)(((int64_t)split * a.n_vt) / a.n_split);
-    const int hi = (int)(((int64_t)(split + 1) * a.n_vt) / a.n_split);
+    const int n_tt = meta_get(a.meta, META_N_TT), n_split = meta_get(a.meta, META_N_SPLIT);
+    const int active = n_tt * n_split;               // the grid is sized for the unmasked worst case
+    tt = split = lo = cnt = 0;
+    if ((int)blockIdx.x >= active) return;
+    const int L = xcd_logical_id(blockIdx.x, active);
+    block_decode(L, n_tt, meta_get(a.meta, META_BA), meta_get(a.meta, META_BB), tt, split);
+    lo = (int)(((int64_t)split * a.n_vt) / n_split);
+    const int hi = (int)(((int64_t)(split + 1) * a.n_vt) / n_split);
     cnt = hi - lo;
   }
   __device__ int n_items() const { return cnt; }
@@ -104,16 +113,18 @@ struct SplitWork {
 // Persistent workgroups striding over the (token tile x vocabulary tile) grid of a chunk.
 struct ChunkWork {
   const LogitArgs& a;
-  int L, G, n_tiles;
+  int L, G, n_tiles, n_tt, ba;
   __device__ ChunkWork(const LogitArgs& a_) : a(a_) {
     G = gridDim.x;
     L = xcd_logical_id(blockIdx.x, G);
-    n_tiles = a.n_tt * a.n_vt;
+    n_tt = meta_get(a.meta, META_N_TT);
+    ba = meta_get(a.meta, META_BA);
+    n_tiles = n_tt * a.n_vt;
   }
   __device__ int n_items() const { return L < n_tiles ? (n_tiles - L + G - 1) / G : 0; }
   __device__ WorkItem item(int i) const {
     int tt, vt;
-    block_decode(i * G + L, a.n_tt, a.ba, a.bb, tt, vt);
+    block_decode(i * G + L, n_tt, ba, a.bb, tt, vt);
     return logit_item(a, a.vt0 + vt, tt);
   }
 };
@@ -368,7 +379,7 @@ KD_LOGIT_KERNEL void stats_kernel(const LogitArgs a) {
   SplitWork work(a);
   StatsEpi<KIND> epi(a.c);
   tile_loop<2, LCfg>(work, epi, a.H_s, a.H_t, a.H_s, a.H_t, smem);
-  epi.write(a, work.tt, work.split);
+  if (work.cnt > 0) epi.write(a, work.tt, work.split);
 }
 
 template <int KIND>
@@ -377,7 +388,7 @@ KD_LOGIT_KERNEL void rows_kernel(const LogitArgs a) {
   SplitWork work(a);
   RowsEpi<KIND> epi(a, work.tt);
   tile_loop<2, LCfg>(work, epi, a.H_s, a.H_t, a.H_s, a.H_t, smem);
-  epi.write(a, work.tt, work.split);
+  if (work.cnt > 0) epi.write(a, work.tt, work.split);
 }
 
 template <int KIND>
@@ -403,30 +414,40 @@ struct GemmArgs {
   int accumulate;      // 1: out += D
   int n_mt, n_nt;
   int ba, bb;          // block shape of the work map (ba | n_mt, bb | n_nt)
+  const int* meta;     // device-side plan (may be null when neither flag below is set)
+  int n_from_meta;     // N = number of valid tokens (rows of the compacted B operand)
+  int k_from_meta;     // K = valid tokens rounded up to whole token tiles
 };
 
 struct GemmWork {
   const GemmArgs& a;
-  int L, G, n_tiles;
+  int L, G, n_tiles, N, K, n_nt, bb;
   __device__ GemmWork(const GemmArgs& a_) : a(a_) {
     G = gridDim.x;
     L = xcd_logical_id(blockIdx.x, G);
-    n_tiles = a.n_mt * a.n_nt * a.n_ksplit;
+    N = a.N; K = a.K; n_nt = a.n_nt; bb = a.bb;
+    if (a.n_from_meta) {
+      N = meta_get(a.meta, META_N_VALID);
+      n_nt = (N + BN - 1) / BN;
+      bb = n_nt % 4 == 0 ? 4 : (n_nt % 3 == 0 ? 3 : (n_nt % 2 == 0 ? 2 : 1));
+    }
+    if (a.k_from_meta) K = meta_get(a.meta, META_T_EFF);
+    n_tiles = a.n_mt * n_nt * a.n_ksplit;
   }
   __device__ int n_items() const { return L < n_tiles ? (n_tiles - L + G - 1) / G : 0; }
   __device__ WorkItem item(int i) const {
     const int q = i * G + L;
-    const int per_split = a.n_mt * a.n_nt;
+    const int per_split = a.n_mt * n_nt;
     const int ks = q / per_split;
     int mt, nt;
-    block_decode(q - ks * per_split, a.n_mt, a.ba, a.bb, mt, nt);
+    block_decode(q - ks * per_split, a.n_mt, a.ba, bb, mt, nt);
     const int k0 = ks * a.ksteps * GCfg::BK;
     WorkItem it;
     it.A0 = it.A1 = a.A + (int64_t)mt * GCfg::BM * a.lda + k0;
     it.B0 = it.B1 = a.B + (int64_t)nt * BN * a.ldb + k0;
     it.a_rows = min(GCfg::BM, a.M - mt * GCfg::BM);
-    it.b_rows = min(BN, a.N - nt * BN);
-    it.nk0 = it.nk1 = min(a.ksteps, a.K / GCfg::BK - ks * a.ksteps);
+    it.b_rows = min(BN, N - nt * BN);
+    it.nk0 = it.nk1 = a.k_from_meta ? K / GCfg::BK : min(a.ksteps, K / GCfg::BK - ks * a.ksteps);
     it.m0 = mt * GCfg::BM;
     it.n0 = nt * BN;
     it.aux = ks;
@@ -488,12 +509,68 @@ KD_GEMM_KERNEL void gemm_kernel(const GemmArgs a) {
 // small kernels
 // ------------------------------------------------------------------------------------------
 
-// Merge the partial statistics of one token; write log-sum-exps and, for FKL / RKL, the row loss.
-__global__ void combine_kernel(const float* partials, int n_parts, int T, int T_pad, int kind, float c,
+// One workgroup.  Compacts the valid tokens (mask != 0; all of them when mask is null) to the front:
+// rowmap[j] = index of the j-th valid token, inv[t] = its compacted index or -1, and writes the
+// device-side plan that depends on how many there are.  Every later kernel works on the compacted
+// token axis, so masked tokens cost nothing.
+__global__ void rowmap_kernel(const uint8_t* mask, int T, int T_pad, int n_split_max, int n_cu,
+                              int* rowmap, int* inv, int* meta) {
+  __shared__ int s_scan[1024];
+  __shared__ int s_running;
+  const int tid = threadIdx.x;
+  if (tid == 0) s_running = 0;
+  __syncthreads();
+  for (int base = 0; base < T; base += 1024) {
+    const int t = base + tid;
+    const int on = (t < T && (mask == nullptr || mask[t] != 0)) ? 1 : 0;
+    s_scan[tid] = on;
+    __syncthreads();
+    for (int d = 1; d < 1024; d <<= 1) {          // inclusive scan
+      const int v = tid >= d ? s_scan[tid - d] : 0;
+      __syncthreads();
+      s_scan[tid] += v;
+      __syncthreads();
+    }
+    const int run = s_running;
+    if (t < T) {
+      const int j = run + s_scan[tid] - on;
+      if (on) rowmap[j] = t;
+      inv[t] = on ? j : -1;
+    }
+    __syncthreads();
+    if (tid == 1023) s_running = run + s_scan[1023];
+    __syncthreads();
+  }
+  const int n = s_running;
+  const int last = n > 0 ? rowmap[n - 1] : 0;
+  __syncthreads();
+  for (int j = n + tid; j < T_pad; j += 1024) rowmap[j] = last;   // never dereferenced for results
+  if (tid == 0) {
+    int n_tt = (n + BN - 1) / BN;
+    if (n_tt < 1) n_tt = 1;
+    int n_split = n_cu / n_tt;                     // as many splits as keep one workgroup per CU
+    if (n_split < 8) n_split = 8;
+    if (n_split > n_split_max) n_split = n_split_max;
+    int ba = 1, bb = 1;
+    for (int d = 2; d <= 4; ++d) if (n_tt % d == 0) ba = d;
+    for (int d = 2; d <= 8; ++d) if (n_split % d == 0) bb = d;
+    meta[META_N_VALID] = n;
+    meta[META_N_TT] = n_tt;
+    meta[META_N_SPLIT] = n_split;
+    meta[META_BA] = ba;
+    meta[META_BB] = bb;
+    meta[META_T_EFF] = n_tt * BN;
+  }
+}
+
+// Merge the partial statistics of one (compacted) token; write log-sum-exps and, for FKL / RKL, the
+// row loss.
+__global__ void combine_kernel(const float* partials, const int* meta, int T_pad, int kind, float c,
                                f32x4* rowinfo, float* row_loss) {
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= T_pad) return;
-  if (t >= T) {   // padding rows: probabilities evaluate to 0, gradient scale 0
+  const int n_valid = meta[META_N_VALID], n_parts = 4 * meta[META_N_SPLIT];
+  if (t >= n_valid) {   // padding rows: probabilities evaluate to 0, gradient scale 0
     rowinfo[t] = f32x4{1.0e30f, 1.0e30f, 0.f, 0.f};
     row_loss[t] = 0.f;
     return;
@@ -521,10 +598,11 @@ __global__ void combine_kernel(const float* partials, int n_parts, int T, int T_
 }
 
 // JSD / TVD / skewed KL: merge the row sums into the row loss and R (see RowTerm).
-__global__ void combine_rows_kernel(const float* partials, int n_parts, int T, int T_pad, int kind, float w,
+__global__ void combine_rows_kernel(const float* partials, const int* meta, int T_pad, int kind, float w,
                                     f32x4* rowinfo, float* row_loss) {
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
-  if (t >= T) return;
+  const int n_valid = meta[META_N_VALID], n_parts = 4 * meta[META_N_SPLIT];
+  if (t >= n_valid) return;
   float A1 = 0.f, A2 = 0.f;
   for (int p = 0; p < n_parts; ++p) {
     const float* q = partials + (int64_t)p * 2 * T_pad + t;
@@ -542,34 +620,29 @@ __global__ void combine_rows_kernel(const float* partials, int n_parts, int T, i
   row_loss[t] = loss;
 }
 
-// One workgroup: n = sum mask, loss = sum mask l / n, per-row gradient scale mask / (n tau).
-__global__ void finalize_kernel(const uint8_t* mask, const float* row_loss, int T, float tau,
+// One workgroup: loss = sum of the valid rows' losses / n (fixed-order fp64 tree), per-row gradient
+// scale 1 / (n tau), and the caller's per-token losses (0 for masked tokens).
+__global__ void finalize_kernel(const int* meta, const int* inv, const float* row_loss, int T, float tau,
                                 f32x4* rowinfo, float* loss_out, float* per_token_out) {
   __shared__ double s_sum[1024];
-  __shared__ int s_cnt[1024];
   const int tid = threadIdx.x;
+  const int n = meta[META_N_VALID];
   double acc = 0.0;
-  int cnt = 0;
-  for (int t = tid; t < T; t += 1024) {
-    const bool on = mask == nullptr || mask[t] != 0;
-    const float l = row_loss[t];
-    if (on) { acc += (double)l; ++cnt; }
-    if (per_token_out) per_token_out[t] = l;
-  }
+  for (int j = tid; j < n; j += 1024) acc += (double)row_loss[j];
   s_sum[tid] = acc;
-  s_cnt[tid] = cnt;
   __syncthreads();
   for (int s = 512; s > 0; s >>= 1) {
-    if (tid < s) { s_sum[tid] += s_sum[tid + s]; s_cnt[tid] += s_cnt[tid + s]; }
+    if (tid < s) s_sum[tid] += s_sum[tid + s];
     __syncthreads();
   }
-  const int n = s_cnt[0];
   if (tid == 0) *loss_out = n > 0 ? (float)(s_sum[0] / (double)n) : 0.f;
   const float scale = n > 0 ? 1.f / ((float)n * tau) : 0.f;
-  for (int t = tid; t < T; t += 1024) {
-    const bool on = mask == nullptr || mask[t] != 0;
-    rowinfo[t][2] = on ? scale : 0.f;
-  }
+  for (int j = tid; j < n; j += 1024) rowinfo[j][2] = scale;
+  if (per_token_out)
+    for (int t = tid; t < T; t += 1024) {
+      const int j = inv[t];
+      per_token_out[t] = j >= 0 ? row_loss[j] : 0.f;
+    }
 }
 
 // dst[c][r] = src[r][c] for r < R, zero for R <= r < R_pad;  c < C.  64 x 64 tiles through LDS.
@@ -594,12 +667,22 @@ __global__ void transpose_kernel(const bf16_t* src, int64_t ld_src, int R, int C
 //   split_mode 1 (heads):         [hi | hi | lo]
 //   split_mode 2 (hidden states): [hi | lo | hi]
 // so that sum_k A'[m][k] B'[n][k] = hi.hi + hi.lo + lo.hi.
-__global__ void prepare_kernel(const void* src, int src_f32, int R, int H, bf16_t* dst, int K, int split_mode) {
+// With a row map, destination row j takes source row rowmap[j] for j < n_valid and is zero beyond:
+// the compacted copy of the hidden states.
+__global__ void prepare_kernel(const void* src, int src_f32, int R, int H, bf16_t* dst, int K, int split_mode,
+                               const int* rowmap, const int* meta) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (int64_t)R * K) return;
-  const int r = (int)(i / K), c = (int)(i % K);
+  int r = (int)(i / K);
+  const int c = (int)(i % K);
   bf16_t v = (bf16_t)0.f;
-  if (!src_f32) {
+  bool live = true;
+  if (rowmap) {
+    live = r < meta[META_N_VALID];
+    r = rowmap[r];
+  }
+  if (!live) {
+  } else if (!src_f32) {
     if (c < H) v = ((const bf16_t*)src)[(int64_t)r * H + c];
   } else if (c < 3 * H) {
     const int part = c / H, col = c - part * H;
@@ -611,12 +694,21 @@ __global__ void prepare_kernel(const void* src, int src_f32, int R, int H, bf16_
   dst[i] = v;
 }
 
-// grad_h_s = sum over split-K parts of the fp32 partial sums, converted to the output dtype.
-__global__ void gradh_finish_kernel(const float* parts, int n_parts, int64_t n, int out_f32, void* out) {
+// grad_h_s row t = sum over split-K parts of the fp32 partial sums of its compacted row (zero for a
+// masked token), converted to the output dtype.
+__global__ void gradh_finish_kernel(const float* parts, int n_parts, int T, int H, const int* inv,
+                                    int out_f32, void* out) {
   const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  const int64_t n = (int64_t)T * H;
   if (i >= n) return;
-  f32x4 v = *(const f32x4*)(parts + i);
-  for (int p = 1; p < n_parts; ++p) v += *(const f32x4*)(parts + (int64_t)p * n + i);
+  const int t = (int)(i / H), h = (int)(i % H);
+  const int j = inv[t];
+  f32x4 v = {0.f, 0.f, 0.f, 0.f};
+  if (j >= 0) {
+    const float* src = parts + (int64_t)j * H + h;
+    v = *(const f32x4*)src;
+    for (int p = 1; p < n_parts; ++p) v += *(const f32x4*)(src + (int64_t)p * n);
+  }
   if (out_f32) {
     *(f32x4*)((float*)out + i) = v;
   } else {
@@ -650,7 +742,7 @@ static LogitArgs make_logit_args(const Problem& p) {
   a.W_s = (const bf16_t*)p.W_s; a.h_s = (const bf16_t*)p.h_s;
   a.W_t = (const bf16_t*)p.W_t; a.h_t = (const bf16_t*)p.h_t;
   a.T = p.T; a.V = p.V; a.H_s = p.K_s; a.H_t = p.K_t;   // contraction lengths = row strides
-  a.n_tt = p.n_tt;
+  a.meta = p.meta;
   a.c = 1.4426950408889634f / p.tau;
   a.beta = p.beta;
   a.T_pad = p.T_pad;
@@ -660,11 +752,9 @@ static LogitArgs make_logit_args(const Problem& p) {
 
 hipError_t launch_stats(const Problem& p, hipStream_t st) {
   LogitArgs a = make_logit_args(p);
-  a.vt0 = 0; a.n_vt = p.n_vt; a.n_split = p.n_split;
-  a.ba = largest_divisor_le(p.n_tt, 4);
-  a.bb = largest_divisor_le(p.n_split, 8);
+  a.vt0 = 0; a.n_vt = p.n_vt;
   a.partials = p.partials;
-  const int grid = p.n_tt * p.n_split;
+  const int grid = p.n_tt * p.n_split;      // worst case; workgroups beyond the device-side plan exit
   switch (p.kind) {
     case 0: return launch_big(stats_kernel<0>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
     case 1: return launch_big(stats_kernel<1>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
@@ -674,9 +764,7 @@ hipError_t launch_stats(const Problem& p, hipStream_t st) {
 
 hipError_t launch_rows(const Problem& p, hipStream_t st) {
   LogitArgs a = make_logit_args(p);
-  a.vt0 = 0; a.n_vt = p.n_vt; a.n_split = p.n_split;
-  a.ba = largest_divisor_le(p.n_tt, 4);
-  a.bb = largest_divisor_le(p.n_split, 8);
+  a.vt0 = 0; a.n_vt = p.n_vt;
   a.partials = p.partials;
   const int grid = p.n_tt * p.n_split;
   switch (p.kind) {
@@ -687,22 +775,26 @@ hipError_t launch_rows(const Problem& p, hipStream_t st) {
   }
 }
 
+hipError_t launch_rowmap(const Problem& p, hipStream_t st) {
+  hipLaunchKernelGGL(rowmap_kernel, dim3(1), dim3(1024), 0, st, p.mask, p.T, p.T_pad, p.n_split, p.n_cu, p.rowmap,
+                     p.inv, p.meta);
+  return hipGetLastError();
+}
+
 hipError_t launch_combine(const Problem& p, hipStream_t st) {
-  const int n_parts = p.n_split * 4;
-  hipLaunchKernelGGL(combine_kernel, dim3((p.T_pad + 255) / 256), dim3(256), 0, st, p.partials, n_parts, p.T,
-                     p.T_pad, p.kind, 1.4426950408889634f / p.tau, (f32x4*)p.rowinfo, p.row_loss);
+  hipLaunchKernelGGL(combine_kernel, dim3((p.T_pad + 255) / 256), dim3(256), 0, st, p.partials, p.meta, p.T_pad,
+                     p.kind, 1.4426950408889634f / p.tau, (f32x4*)p.rowinfo, p.row_loss);
   return hipGetLastError();
 }
 
 hipError_t launch_combine_rows(const Problem& p, hipStream_t st) {
-  const int n_parts = p.n_split * 4;
-  hipLaunchKernelGGL(combine_rows_kernel, dim3((p.T + 255) / 256), dim3(256), 0, st, p.partials, n_parts, p.T,
-                     p.T_pad, p.kind, p.beta, (f32x4*)p.rowinfo, p.row_loss);
+  hipLaunchKernelGGL(combine_rows_kernel, dim3((p.T + 255) / 256), dim3(256), 0, st, p.partials, p.meta, p.T_pad,
+                     p.kind, p.beta, (f32x4*)p.rowinfo, p.row_loss);
   return hipGetLastError();
 }
 
 hipError_t launch_finalize(const Problem& p, hipStream_t st) {
-  hipLaunchKernelGGL(finalize_kernel, dim3(1), dim3(1024), 0, st, p.mask, p.row_loss, p.T, p.tau,
+  hipLaunchKernelGGL(finalize_kernel, dim3(1), dim3(1024), 0, st, p.meta, p.inv, p.row_loss, p.T, p.tau,
                      (f32x4*)p.rowinfo, p.loss, p.per_token_loss);
   return hipGetLastError();
 }
@@ -711,7 +803,6 @@ hipError_t launch_grad_chunk(const Problem& p, int v0, int width, hipStream_t st
   LogitArgs a = make_logit_args(p);
   a.vt0 = v0 / BM;
   a.n_vt = (width + BM - 1) / BM;
-  a.ba = largest_divisor_le(p.n_tt, 4);
   a.bb = largest_divisor_le(a.n_vt, 8);
   a.dz = (bf16_t*)p.dz; a.dzT = (bf16_t*)p.dzT; a.ldz = p.V_c;
   const int tiles = p.n_tt * a.n_vt;
@@ -747,16 +838,17 @@ hipError_t launch_gemm(const GemmDesc& d, int n_cu, hipStream_t st) {
   a.n_nt = (d.N + BN - 1) / BN;
   a.ba = largest_divisor_le(a.n_mt, 8);
   a.bb = largest_divisor_le(a.n_nt, 4);
-  const int tiles = a.n_mt * a.n_nt * a.n_ksplit;
+  a.meta = d.meta; a.n_from_meta = d.n_from_meta; a.k_from_meta = d.k_from_meta;
+  const int tiles = a.n_mt * a.n_nt * a.n_ksplit;       // worst case (no token masked)
   const int grid = tiles < n_cu ? tiles : n_cu;
   return launch_big(gemm_kernel, grid, GCfg::NT, GCfg::SMEM_BYTES, st, &a);
 }
 
 hipError_t launch_prepare(const void* src, int src_f32, int R, int H, void* dst, int K, int split_mode,
-                          hipStream_t st) {
+                          const int* rowmap, const int* meta, hipStream_t st) {
   const int64_t n = (int64_t)R * K;
   hipLaunchKernelGGL(prepare_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, src, src_f32, R, H,
-                     (bf16_t*)dst, K, split_mode);
+                     (bf16_t*)dst, K, split_mode, rowmap, meta);
   return hipGetLastError();
 }
 
@@ -764,7 +856,7 @@ hipError_t launch_gradh_finish(const Problem& p, hipStream_t st) {
   const int64_t n = (int64_t)p.T * p.H_s;
   const int64_t threads = (n + 3) / 4;
   hipLaunchKernelGGL(gradh_finish_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, p.gh32,
-                     p.n_ksplit_h, n, p.grad_f32, p.grad_h_s);
+                     p.n_ksplit_h, p.T, p.H_s, p.inv, p.grad_f32, p.grad_h_s);
   return hipGetLastError();
 }
 

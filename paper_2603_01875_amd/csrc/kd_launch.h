@@ -23,7 +23,8 @@ struct Problem {
   int accumulate_grad_W;
   const void *h_t, *W_t, *h_s, *W_s;                   // bf16 [rows][K_t or K_s] as the kernels read them
   const void *user_h_t, *user_W_t, *user_h_s, *user_W_s;  // the caller's arrays
-  int in_f32, prep_t, prep_s;   // inputs are fp32; teacher / student operands are re-packed into the workspace
+  int in_f32;                   // inputs are fp32
+  int prep_ht, prep_Wt, prep_hs, prep_Ws;   // which operands are re-packed into the workspace
   int K_t, K_s;                 // contraction lengths of the (re-packed) logit operands, multiples of 64
   const uint8_t* mask;
   float* loss;
@@ -32,6 +33,9 @@ struct Problem {
   // plan
   int T_pad, n_tt, n_vt, n_split, V_c, n_ksplit_h, ksteps_h, n_cu;
   // workspace carve-up
+  int* meta;           // device-side plan written by the row-map kernel
+  int* rowmap;         // [T_pad] compacted index -> token
+  int* inv;            // [T] token -> compacted index or -1
   float* rowinfo;      // [T_pad][4]
   float* row_loss;     // [T_pad]
   float* partials;     // [n_split*4][5][T_pad]
@@ -52,8 +56,12 @@ struct GemmDesc {
   void* out;
   int64_t ldo, out_split_stride;
   int out_f32, accumulate;
+  const int* meta;        // device-side plan, needed when a flag below is set
+  int n_from_meta;        // N = number of valid tokens
+  int k_from_meta;        // K = valid tokens rounded up to whole token tiles (no split-K)
 };
 
+hipError_t launch_rowmap(const Problem& p, hipStream_t st);
 hipError_t launch_stats(const Problem& p, hipStream_t st);
 hipError_t launch_combine(const Problem& p, hipStream_t st);
 hipError_t launch_rows(const Problem& p, hipStream_t st);
@@ -66,6 +74,6 @@ hipError_t launch_gemm(const GemmDesc& d, int n_cu, hipStream_t st);
 hipError_t launch_gradh_finish(const Problem& p, hipStream_t st);
 // dst bf16 [R][K]: mode 0 = copy, 1 = fp32 split as [hi|hi|lo], 2 = fp32 split as [hi|lo|hi]; zero-padded to K
 hipError_t launch_prepare(const void* src, int src_f32, int R, int H, void* dst, int K, int split_mode,
-                          hipStream_t st);
+                          const int* rowmap, const int* meta, hipStream_t st);
 
 }  // namespace kd

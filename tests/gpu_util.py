@@ -34,8 +34,11 @@ def run_gpu(cfg, data, **kw):
 
 
 def run_oracle(cfg, data):
-    return O.kd_loss_fwd_bwd(data["h_t"], data["W_t"], data["h_s"], data["W_s"], data["mask"], cfg.tau,
-                             cfg.kind, cfg.beta, O.W_VH)
+    ref = O.kd_loss_fwd_bwd(data["h_t"], data["W_t"], data["h_s"], data["W_s"], data["mask"], cfg.tau,
+                            cfg.kind, cfg.beta, O.W_VH)
+    if data["mask"] is not None:        # the library reports 0 for masked tokens (it never computes them)
+        ref["per_token_loss"] = ref["per_token_loss"] * (np.asarray(data["mask"]) != 0)
+    return ref
 
 
 def tvd_tie_allowance(cfg, data, rel_gap=2e-5):

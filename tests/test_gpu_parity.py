@@ -140,3 +140,18 @@ def test_tvd_peaked_teacher():
     cfg = I.scaled(I.workload("long_peaked"), batch=1, seq=256, H_t=1024, H_s=256, V=4096, kind=I.TVD)
     data = I.generate(cfg)
     G.check(G.run_gpu(cfg, data), G.run_oracle(cfg, data), "tvd peaked", G.tvd_tie_allowance(cfg, data))
+
+
+@pytest.mark.parametrize("keep", [1, 37, 300, 700])
+def test_heavy_masks_are_compacted_correctly(keep):
+    # T=768 (3 token tiles); only `keep` scattered tokens are valid, so whole tiles disappear
+    cfg = I.scaled(I.workload("jsd_bf16"), batch=3, seq=256, H_t=128, H_s=64, V=1544, mask="ones")
+    data = I.generate(cfg)
+    rng = np.random.default_rng(keep)
+    mask = np.zeros(cfg.T, np.uint8)
+    mask[rng.choice(cfg.T, size=keep, replace=False)] = 1
+    data = dict(data, mask=mask)
+    out = G.run_gpu(cfg, data)
+    G.check(out, G.run_oracle(cfg, data), f"keep={keep}")
+    ptl = G.to_host(out["per_token_loss"]); gh = G.to_host(out["grad_h_s"])
+    assert (ptl[mask == 0] == 0).all() and (gh[mask == 0] == 0).all()
