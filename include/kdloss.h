@@ -45,7 +45,7 @@ typedef enum {
   KD_ERR_NULL = 1,        /* a required pointer is NULL                          */
   KD_ERR_SHAPE = 2,       /* T, H_t, H_s or V < 1, or beyond the supported range */
   KD_ERR_ALIGN = 3,       /* pointer not 16-byte aligned, or H_t/H_s/V % 8 != 0  */
-  KD_ERR_PARAM = 4,       /* tau <= 0 or not finite, unknown enum, beta outside (0,1) where it is used */
+  KD_ERR_PARAM = 4,       /* tau outside [1e-6, 1e6] or not finite, unknown enum, beta outside (0,1) where it is used */
   KD_ERR_WORKSPACE = 5,   /* workspace_bytes smaller than kd_loss_workspace_size */
   KD_ERR_UNSUPPORTED = 6, /* valid request this build does not implement         */
   KD_ERR_LAUNCH = 7       /* the HIP runtime refused a launch (see hipGetLastError) */
@@ -65,6 +65,11 @@ typedef enum { KD_BF16 = 0, KD_F32 = 1 } kd_dtype;
  * The same order applies to W_t, W_s and grad_W_s. */
 typedef enum { KD_W_HV = 0, KD_W_VH = 1 } kd_wlayout;
 
+/* KD_FLAG_TAU2: multiply the loss, the per-token losses and both gradients by tau^2 (the
+ * convention that keeps gradient magnitudes independent of the temperature).  Off by default:
+ * the paper does not mention it. */
+typedef enum { KD_FLAG_TAU2 = 1 } kd_flags;
+
 typedef struct {
   int64_t T;            /* tokens (batch x sequence, flattened)                     */
   int64_t H_t, H_s;     /* teacher / student hidden sizes, multiples of 8           */
@@ -73,12 +78,12 @@ typedef struct {
   int32_t grad_dtype;   /* kd_dtype of grad_h_s and grad_W_s                        */
   int32_t w_layout;     /* kd_wlayout                                               */
   int32_t kind;         /* kd_kind                                                  */
-  float tau;            /* temperature, > 0                                         */
+  float tau;            /* temperature, 1e-6 <= tau <= 1e6                          */
   float beta;           /* JSD mixing weight on the teacher term, or the skew weight
                            of the skewed KLs; 0 < beta < 1; ignored for FKL/RKL/TVD */
   int32_t accumulate_grad_W; /* 0: grad_W_s is overwritten. 1: added to (gradient
                            accumulation over micro-batches, Table 3 caption)        */
-  int32_t reserved;     /* must be 0                                                */
+  int32_t flags;        /* bit set of kd_flags; other bits must be 0                */
 } kd_loss_params;
 
 /* Bytes of device workspace kd_loss_fwd_bwd needs for these parameters.
@@ -125,6 +130,23 @@ kd_status kd_loss_fwd(const kd_loss_params* params,
                       float* loss, float* per_token_loss,
                       void* workspace, size_t workspace_bytes,
                       void* hip_stream);
+
+/* Multi-teacher distillation (Table 1, "Multi-Teacher Distillation"): n_teachers teachers over the
+ * same tokens and vocabulary, each with its own hidden states h_t[k] [T, H_t[k]] and head W_t[k];
+ *   loss = sum_k weights[k] * D(p_t^k, p_s)      (same divergence, temperature and mask for all)
+ * and the gradients are those of that sum.  params->H_t is ignored; h_t, W_t, H_t, weights are HOST
+ * arrays of n_teachers entries (the pointers in h_t / W_t are device pointers).  1 <= n_teachers <= 16.
+ * Everything else is as for kd_loss_fwd_bwd; the workspace must satisfy the _multi size query.  The
+ * student logits are recomputed once per teacher; grad_h_s is accumulated over teachers in fp32,
+ * grad_W_s in the output dtype. */
+kd_status kd_loss_workspace_size_multi(const kd_loss_params* params, int n_teachers, const int64_t* H_t,
+                                       size_t* bytes);
+kd_status kd_loss_fwd_bwd_multi(const kd_loss_params* params, int n_teachers,
+                                const void* const* h_t, const void* const* W_t, const int64_t* H_t,
+                                const float* weights,
+                                const void* h_s, const void* W_s, const uint8_t* mask,
+                                float* loss, float* per_token_loss, void* grad_h_s, void* grad_W_s,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char* kd_status_string(kd_status status);

@@ -154,7 +154,7 @@ def kd_loss_from_logits(z_t, z_s, mask=None, tau=1.0, kind=FKL, beta=0.5):
 
 
 def kd_loss_fwd_bwd(h_t, W_t, h_s, W_s, mask=None, tau=1.0, kind=FKL, beta=0.5,
-                    w_layout=W_HV, row_block=512):
+                    w_layout=W_HV, row_block=512, tau2=False):
     """The whole hot path in fp64.
 
     Returns dict(loss, per_token_loss[T], n, grad_h_s[T,H_s], grad_W_s) with
@@ -186,8 +186,26 @@ def kd_loss_fwd_bwd(h_t, W_t, h_s, W_s, mask=None, tau=1.0, kind=FKL, beta=0.5,
     loss = float((m * per_tok).sum() / n) if n > 0 else 0.0
     if w_layout == W_VH:
         grad_W = np.ascontiguousarray(grad_W.T)
+    if tau2:                       # optional convention: everything times tau^2
+        f = float(tau) ** 2
+        loss, per_tok, grad_h, grad_W = loss * f, per_tok * f, grad_h * f, grad_W * f
     return dict(loss=loss, per_token_loss=per_tok, n=int(n),
                 grad_h_s=grad_h, grad_W_s=grad_W)
+
+
+def kd_loss_multi(h_ts, W_ts, weights, h_s, W_s, mask=None, tau=1.0, kind=FKL, beta=0.5,
+                  w_layout=W_HV, row_block=512):
+    """Multi-teacher distillation (Table 1): loss = sum_k weights[k] D(p_t^k, p_s); by linearity the
+    outputs are the weighted sums of the single-teacher outputs."""
+    tot = None
+    for w, h_t, W_t in zip(weights, h_ts, W_ts):
+        r = kd_loss_fwd_bwd(h_t, W_t, h_s, W_s, mask, tau, kind, beta, w_layout, row_block)
+        if tot is None:
+            tot = {k: (w * v if k != "n" else v) for k, v in r.items()}
+        else:
+            for k in ("loss", "per_token_loss", "grad_h_s", "grad_W_s"):
+                tot[k] = tot[k] + w * r[k]
+    return tot
 
 
 def row_lse(h, W, tau=1.0, w_layout=W_HV, row_block=512):

@@ -27,12 +27,12 @@ kd_status check_params(const kd_loss_params* p) {
   if (p->grad_dtype != KD_BF16 && p->grad_dtype != KD_F32) return KD_ERR_PARAM;
   if (p->w_layout != KD_W_HV && p->w_layout != KD_W_VH) return KD_ERR_PARAM;
   if (p->kind < KD_FKL || p->kind > KD_SKEW_RKL) return KD_ERR_PARAM;
-  if (!(p->tau > 0.f) || !std::isfinite(p->tau)) return KD_ERR_PARAM;
+  if (!(p->tau >= 1e-6f && p->tau <= 1e6f)) return KD_ERR_PARAM;   // also rejects NaN
   if ((p->kind == KD_JSD || p->kind == KD_SKEW_FKL || p->kind == KD_SKEW_RKL) &&
       !(p->beta > 0.f && p->beta < 1.f))
     return KD_ERR_PARAM;
   if (p->accumulate_grad_W != 0 && p->accumulate_grad_W != 1) return KD_ERR_PARAM;
-  if (p->reserved != 0) return KD_ERR_PARAM;
+  if (p->flags & ~(int32_t)KD_FLAG_TAU2) return KD_ERR_PARAM;
   if (p->w_layout != KD_W_VH) return KD_ERR_UNSUPPORTED;
   return KD_OK;
 }
@@ -43,6 +43,8 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward) {
   q.kind = p->kind; q.tau = p->tau; q.beta = p->beta;
   q.grad_f32 = p->grad_dtype == KD_F32;
   q.accumulate_grad_W = p->accumulate_grad_W;
+  q.out_weight = (p->flags & KD_FLAG_TAU2) ? p->tau * p->tau : 1.f;
+  q.accumulate_loss = 0;
   q.n_cu = kd::kNumCU;
   // Operands as the kernels want them: bf16, K-contiguous, K a multiple of 64.  fp32 inputs are
   // split into bf16 high and low parts laid side by side along K (three products recover all
@@ -101,8 +103,6 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward) {
   L.row_loss = take((size_t)q.T_pad * 4);
   L.partials = take((size_t)q.n_split * 4 * 5 * q.T_pad * 4);
   L.prep_h_t = L.prep_W_t = L.prep_h_s = L.prep_W_s = 0;
-  if (q.prep_ht) L.prep_h_t = take((size_t)q.T * q.K_t * 2);
-  if (q.prep_Wt) L.prep_W_t = take((size_t)q.V * q.K_t * 2);
   if (q.prep_hs) L.prep_h_s = take((size_t)q.T * q.K_s * 2);
   if (q.prep_Ws) L.prep_W_s = take((size_t)q.V * q.K_s * 2);
   if (with_backward) {
@@ -114,6 +114,10 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward) {
   } else {
     L.h_sT = L.W_sT = L.dz = L.dzT = L.gh32 = off;
   }
+  // the only buffers whose size depends on the teacher come last, so that everything above sits at
+  // the same offsets for every teacher of a multi-teacher call
+  if (q.prep_ht) L.prep_h_t = take((size_t)q.T * q.K_t * 2);
+  if (q.prep_Wt) L.prep_W_t = take((size_t)q.V * q.K_t * 2);
   L.total = off;
 }
 
@@ -211,6 +215,53 @@ kd_status run_forward(const Problem& q, hipStream_t st) {
   return KD_OK;
 }
 
+// Backward pass of one teacher: dL/dz_s chunk by chunk and the two products.  grad_h_s is summed in
+// fp32 over the chunks (and over teachers) and converted once, after the last teacher.
+kd_status run_backward(const Problem& q, hipStream_t st, bool first_teacher, bool last_teacher) {
+  // h_s^T [H_s][T_pad] once (token axis zero-padded): the K-contiguous operand of grad_W_s
+  KD_TRY(kd::launch_transpose(q.h_s, q.K_s, q.T, q.H_s, q.h_sT, q.T_pad, q.T_pad, st));
+
+  const size_t gsz = q.grad_f32 ? 4 : 2;
+  bool first = first_teacher;      // the fp32 partial sums of grad_h_s run on across teachers
+  for (int64_t v0 = 0; v0 < q.V; v0 += q.V_c) {
+    const int width = (int)((q.V - v0 < q.V_c) ? q.V - v0 : q.V_c);
+    {
+      ProfileScope ps(KD_PROF_GRAD, st);
+      KD_TRY(kd::launch_grad_chunk(q, (int)v0, width, st));
+    }
+    // W_s[chunk]^T [H_s][V_c]: the K-contiguous operand of grad_h_s
+    KD_TRY(kd::launch_transpose(static_cast<const char*>(q.W_s) + (size_t)v0 * q.K_s * 2, q.K_s, width, q.H_s,
+                                q.W_sT, q.V_c, (int)round_up(width, 64), st));
+    kd::GemmDesc gw{};   // grad_W_s[v][h] = sum_t h_sT[h][t] dzT[v][t]
+    gw.A = q.h_sT; gw.lda = q.T_pad; gw.M = q.H_s;
+    gw.B = q.dzT; gw.ldb = q.T_pad; gw.N = width;
+    gw.K = q.T_pad; gw.k_per_split = 0;
+    gw.meta = q.meta; gw.k_from_meta = 1;        // only the token tiles that hold valid tokens
+    gw.out = static_cast<char*>(q.grad_W_s) + (size_t)v0 * q.H_s * gsz;
+    gw.ldo = q.H_s; gw.out_split_stride = 0;
+    gw.out_f32 = q.grad_f32; gw.accumulate = q.accumulate_grad_W;
+    {
+      ProfileScope ps(KD_PROF_GEMM_GRAD_W, st);
+      KD_TRY(kd::launch_gemm(gw, q.n_cu, st));
+    }
+    kd::GemmDesc gh{};   // grad_h_s[t][h] += sum_v W_sT[h][v] dz[t][v]
+    gh.A = q.W_sT; gh.lda = q.V_c; gh.M = q.H_s;
+    gh.B = q.dz; gh.ldb = q.V_c; gh.N = q.T;
+    gh.meta = q.meta; gh.n_from_meta = 1;        // rows = valid tokens
+    gh.K = (int)round_up(width, 64); gh.k_per_split = q.ksteps_h * 64;
+    gh.out = q.gh32; gh.ldo = q.H_s; gh.out_split_stride = (int64_t)q.T * q.H_s;
+    gh.out_f32 = 1; gh.accumulate = first ? 0 : 1;
+    {
+      ProfileScope ps(KD_PROF_GEMM_GRAD_H, st);
+      KD_TRY(kd::launch_gemm(gh, q.n_cu, st));
+    }
+    first = false;
+  }
+  if (last_teacher) KD_TRY(kd::launch_gradh_finish(q, st));
+  return KD_OK;
+}
+
+
 kd_status check_buffers(const kd_loss_params* params, const void* h_t, const void* W_t, const void* h_s,
                         const void* W_s, const uint8_t* mask, float* loss, void* workspace,
                         size_t workspace_bytes, bool backward, void* grad_h_s, void* grad_W_s,
@@ -284,47 +335,58 @@ kd_status kd_loss_fwd_bwd(const kd_loss_params* params, const void* h_t, const v
 
   s = run_forward(q, st);
   if (s != KD_OK) return s;
+  return run_backward(q, st, true, true);
+}
 
-  // h_s^T [H_s][T_pad] once (token axis zero-padded): the K-contiguous operand of grad_W_s
-  KD_TRY(kd::launch_transpose(q.h_s, q.K_s, q.T, q.H_s, q.h_sT, q.T_pad, q.T_pad, st));
-
-  const size_t gsz = q.grad_f32 ? 4 : 2;
-  bool first = true;
-  for (int64_t v0 = 0; v0 < q.V; v0 += q.V_c) {
-    const int width = (int)((q.V - v0 < q.V_c) ? q.V - v0 : q.V_c);
-    {
-      ProfileScope ps(KD_PROF_GRAD, st);
-      KD_TRY(kd::launch_grad_chunk(q, (int)v0, width, st));
-    }
-    // W_s[chunk]^T [H_s][V_c]: the K-contiguous operand of grad_h_s
-    KD_TRY(kd::launch_transpose(static_cast<const char*>(q.W_s) + (size_t)v0 * q.K_s * 2, q.K_s, width, q.H_s,
-                                q.W_sT, q.V_c, (int)round_up(width, 64), st));
-    kd::GemmDesc gw{};   // grad_W_s[v][h] = sum_t h_sT[h][t] dzT[v][t]
-    gw.A = q.h_sT; gw.lda = q.T_pad; gw.M = q.H_s;
-    gw.B = q.dzT; gw.ldb = q.T_pad; gw.N = width;
-    gw.K = q.T_pad; gw.k_per_split = 0;
-    gw.meta = q.meta; gw.k_from_meta = 1;        // only the token tiles that hold valid tokens
-    gw.out = static_cast<char*>(q.grad_W_s) + (size_t)v0 * q.H_s * gsz;
-    gw.ldo = q.H_s; gw.out_split_stride = 0;
-    gw.out_f32 = q.grad_f32; gw.accumulate = q.accumulate_grad_W;
-    {
-      ProfileScope ps(KD_PROF_GEMM_GRAD_W, st);
-      KD_TRY(kd::launch_gemm(gw, q.n_cu, st));
-    }
-    kd::GemmDesc gh{};   // grad_h_s[t][h] += sum_v W_sT[h][v] dz[t][v]
-    gh.A = q.W_sT; gh.lda = q.V_c; gh.M = q.H_s;
-    gh.B = q.dz; gh.ldb = q.V_c; gh.N = q.T;
-    gh.meta = q.meta; gh.n_from_meta = 1;        // rows = valid tokens
-    gh.K = (int)round_up(width, 64); gh.k_per_split = q.ksteps_h * 64;
-    gh.out = q.gh32; gh.ldo = q.H_s; gh.out_split_stride = (int64_t)q.T * q.H_s;
-    gh.out_f32 = 1; gh.accumulate = first ? 0 : 1;
-    {
-      ProfileScope ps(KD_PROF_GEMM_GRAD_H, st);
-      KD_TRY(kd::launch_gemm(gh, q.n_cu, st));
-    }
-    first = false;
+kd_status kd_loss_workspace_size_multi(const kd_loss_params* params, int n_teachers, const int64_t* H_t,
+                                       size_t* bytes) {
+  if (!bytes || !params || !H_t) return KD_ERR_NULL;
+  if (n_teachers < 1 || n_teachers > 16) return KD_ERR_PARAM;
+  size_t need = 0;
+  for (int k = 0; k < n_teachers; ++k) {
+    kd_loss_params pk = *params;
+    pk.H_t = H_t[k];
+    size_t b = 0;
+    kd_status s = kd_loss_workspace_size(&pk, &b);
+    if (s != KD_OK) return s;
+    if (b > need) need = b;
   }
-  KD_TRY(kd::launch_gradh_finish(q, st));
+  *bytes = need;
+  return KD_OK;
+}
+
+kd_status kd_loss_fwd_bwd_multi(const kd_loss_params* params, int n_teachers, const void* const* h_t,
+                                const void* const* W_t, const int64_t* H_t, const float* weights,
+                                const void* h_s, const void* W_s, const uint8_t* mask, float* loss,
+                                float* per_token_loss, void* grad_h_s, void* grad_W_s, void* workspace,
+                                size_t workspace_bytes, void* hip_stream) {
+  if (!params || !h_t || !W_t || !H_t || !weights) return KD_ERR_NULL;
+  if (n_teachers < 1 || n_teachers > 16) return KD_ERR_PARAM;
+  // all checks for all teachers before the first launch
+  Problem q[16];
+  Layout L[16];
+  for (int k = 0; k < n_teachers; ++k) {
+    if (!std::isfinite(weights[k])) return KD_ERR_PARAM;
+    kd_loss_params pk = *params;
+    pk.H_t = H_t[k];
+    q[k] = Problem{};
+    kd_status s = check_buffers(&pk, h_t[k], W_t[k], h_s, W_s, mask, loss, workspace, workspace_bytes, true,
+                                grad_h_s, grad_W_s, q[k], L[k]);
+    if (s != KD_OK) return s;
+    q[k].per_token_loss = per_token_loss;
+    q[k].out_weight *= weights[k];
+    q[k].accumulate_loss = k > 0;
+    if (k > 0) q[k].accumulate_grad_W = 1;
+  }
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  for (int k = 0; k < n_teachers; ++k) {
+    // the fp32 partial sums of grad_h_s carry over from teacher to teacher: their offset in the
+    // workspace does not depend on H_t (the teacher operand copies are carved last)
+    kd_status s = run_forward(q[k], st);
+    if (s != KD_OK) return s;
+    s = run_backward(q[k], st, k == 0, k + 1 == n_teachers);
+    if (s != KD_OK) return s;
+  }
   return KD_OK;
 }
 

@@ -132,7 +132,11 @@ struct ChunkWork {
 // ------------------------------------------------------------------------------------------
 // epilogues of the logit tiles
 // ------------------------------------------------------------------------------------------
-constexpr float NEG_BIG = -1.0e30f;
+constexpr float NEG_BIG = -1.0e30f;   // logit given to vocabulary rows beyond V: every exp of it is 0
+// Running maxima start here, far below any real scaled logit and far above NEG_BIG * c (the host
+// bounds tau so that c > 1e-9): a lane that has seen only masked rows keeps this maximum, so the
+// exponent of a masked entry stays hugely negative instead of cancelling to a rounding residual.
+constexpr float M_FLOOR = -1.0e20f;
 constexpr float LN2 = 0.6931471805599453f;
 
 __device__ __forceinline__ float fexp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -168,7 +172,7 @@ struct StatsEpi {
     wm = (threadIdx.x >> 6) & 1;
     wn = threadIdx.x >> 7;
 #pragma unroll
-    for (int nt = 0; nt < NI; ++nt) { m_t[nt] = NEG_BIG; m_s[nt] = NEG_BIG; S_t[nt] = 0.f; S_s[nt] = 0.f; X[nt] = 0.f; }
+    for (int nt = 0; nt < NI; ++nt) { m_t[nt] = M_FLOOR; m_s[nt] = M_FLOOR; S_t[nt] = 0.f; S_s[nt] = 0.f; X[nt] = 0.f; }
   }
   __device__ void begin_item(const WorkItem&) {}
   __device__ void end_item(const WorkItem& it, AccTile& accS, AccTile& accT) {
@@ -575,7 +579,7 @@ __global__ void combine_kernel(const float* partials, const int* meta, int T_pad
     row_loss[t] = 0.f;
     return;
   }
-  float Mt = NEG_BIG, Ms = NEG_BIG;
+  float Mt = M_FLOOR, Ms = M_FLOOR;
   for (int p = 0; p < n_parts; ++p) {
     const float* q = partials + (int64_t)p * 5 * T_pad + t;
     Mt = fmaxf(Mt, q[0]);
@@ -622,8 +626,11 @@ __global__ void combine_rows_kernel(const float* partials, const int* meta, int 
 
 // One workgroup: loss = sum of the valid rows' losses / n (fixed-order fp64 tree), per-row gradient
 // scale 1 / (n tau), and the caller's per-token losses (0 for masked tokens).
+// `weight` scales what leaves the call (teacher weight, optional tau^2); with `accumulate` the loss
+// outputs are added to (further teachers of a multi-teacher call).
 __global__ void finalize_kernel(const int* meta, const int* inv, const float* row_loss, int T, float tau,
-                                f32x4* rowinfo, float* loss_out, float* per_token_out) {
+                                float weight, int accumulate, f32x4* rowinfo, float* loss_out,
+                                float* per_token_out) {
   __shared__ double s_sum[1024];
   const int tid = threadIdx.x;
   const int n = meta[META_N_VALID];
@@ -635,13 +642,17 @@ __global__ void finalize_kernel(const int* meta, const int* inv, const float* ro
     if (tid < s) s_sum[tid] += s_sum[tid + s];
     __syncthreads();
   }
-  if (tid == 0) *loss_out = n > 0 ? (float)(s_sum[0] / (double)n) : 0.f;
-  const float scale = n > 0 ? 1.f / ((float)n * tau) : 0.f;
+  if (tid == 0) {
+    const float l = n > 0 ? weight * (float)(s_sum[0] / (double)n) : 0.f;
+    *loss_out = accumulate ? *loss_out + l : l;
+  }
+  const float scale = n > 0 ? weight / ((float)n * tau) : 0.f;
   for (int j = tid; j < n; j += 1024) rowinfo[j][2] = scale;
   if (per_token_out)
     for (int t = tid; t < T; t += 1024) {
       const int j = inv[t];
-      per_token_out[t] = j >= 0 ? row_loss[j] : 0.f;
+      const float l = j >= 0 ? weight * row_loss[j] : 0.f;
+      per_token_out[t] = accumulate ? per_token_out[t] + l : l;
     }
 }
 
@@ -795,7 +806,7 @@ hipError_t launch_combine_rows(const Problem& p, hipStream_t st) {
 
 hipError_t launch_finalize(const Problem& p, hipStream_t st) {
   hipLaunchKernelGGL(finalize_kernel, dim3(1), dim3(1024), 0, st, p.meta, p.inv, p.row_loss, p.T, p.tau,
-                     (f32x4*)p.rowinfo, p.loss, p.per_token_loss);
+                     p.out_weight, p.accumulate_loss, (f32x4*)p.rowinfo, p.loss, p.per_token_loss);
   return hipGetLastError();
 }
 

@@ -21,6 +21,8 @@ struct Problem {
   float tau, beta;
   int grad_f32;
   int accumulate_grad_W;
+  float out_weight;        // factor on the loss and the gradients of this call (teacher weight, tau^2)
+  int accumulate_loss;     // add to *loss and per_token_loss instead of overwriting them
   const void *h_t, *W_t, *h_s, *W_s;                   // bf16 [rows][K_t or K_s] as the kernels read them
   const void *user_h_t, *user_W_t, *user_h_s, *user_W_s;  // the caller's arrays
   int in_f32;                   // inputs are fp32

@@ -26,7 +26,7 @@ class KdLossParams(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int64), ("H_t", ctypes.c_int64), ("H_s", ctypes.c_int64), ("V", ctypes.c_int64),
                 ("in_dtype", ctypes.c_int32), ("grad_dtype", ctypes.c_int32), ("w_layout", ctypes.c_int32),
                 ("kind", ctypes.c_int32), ("tau", ctypes.c_float), ("beta", ctypes.c_float),
-                ("accumulate_grad_W", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("accumulate_grad_W", ctypes.c_int32), ("flags", ctypes.c_int32)]
 
 
 class KdLossError(RuntimeError):
@@ -55,6 +55,13 @@ def lib():
         L.kd_loss_fwd_bwd.restype = ctypes.c_int
         L.kd_loss_fwd.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.kd_loss_fwd.restype = ctypes.c_int
+        L.kd_loss_workspace_size_multi.argtypes = [P, ctypes.c_int, ctypes.POINTER(ctypes.c_int64),
+                                                   ctypes.POINTER(ctypes.c_size_t)]
+        L.kd_loss_workspace_size_multi.restype = ctypes.c_int
+        L.kd_loss_fwd_bwd_multi.argtypes = [P, ctypes.c_int, ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                            ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_float),
+                                            vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.kd_loss_fwd_bwd_multi.restype = ctypes.c_int
         L.kd_loss_profile_hook.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_void_p), ctypes.c_int]
         L.kd_loss_profile_hook.restype = ctypes.c_int
         L.kd_loss_profile_count.argtypes = []
@@ -65,12 +72,15 @@ def lib():
     return _lib
 
 
+FLAG_TAU2 = 1
+
+
 def make_params(T, H_t, H_s, V, kind=FKL, tau=1.0, beta=0.5, in_dtype=BF16, grad_dtype=None,
-                w_layout=W_VH, accumulate_grad_W=False):
+                w_layout=W_VH, accumulate_grad_W=False, flags=0):
     if grad_dtype is None:
         grad_dtype = in_dtype
     return KdLossParams(int(T), int(H_t), int(H_s), int(V), int(in_dtype), int(grad_dtype), int(w_layout),
-                        int(kind), float(tau), float(beta), int(bool(accumulate_grad_W)), 0)
+                        int(kind), float(tau), float(beta), int(bool(accumulate_grad_W)), int(flags))
 
 
 def kd_loss_workspace_size(params: KdLossParams) -> int:
@@ -157,7 +167,7 @@ def alloc_workspace(params, device="cuda"):
 
 def kd_loss_fwd_bwd(h_t, W_t, h_s, W_s, mask=None, tau=1.0, kind=FKL, beta=0.5, w_layout=W_VH,
                     grad_dtype=None, workspace=None, grad_W_s=None, accumulate_grad_W=False,
-                    want_per_token=True):
+                    want_per_token=True, flags=0):
     """Convenience wrapper: allocates outputs (and the workspace unless given) and calls the library.
 
     h_t [T,H_t], h_s [T,H_s]; W_t, W_s in `w_layout` ([V,H] for W_VH).  Returns a dict of CUDA tensors.
@@ -169,7 +179,7 @@ def kd_loss_fwd_bwd(h_t, W_t, h_s, W_s, mask=None, tau=1.0, kind=FKL, beta=0.5, 
     V = W_t.shape[0] if w_layout == W_VH else W_t.shape[1]
     if grad_dtype is None:
         grad_dtype = in_dtype
-    p = make_params(T, H_t, H_s, V, kind, tau, beta, in_dtype, grad_dtype, w_layout, accumulate_grad_W)
+    p = make_params(T, H_t, H_s, V, kind, tau, beta, in_dtype, grad_dtype, w_layout, accumulate_grad_W, flags)
     tdt = torch.bfloat16 if grad_dtype == BF16 else torch.float32
     dev = h_t.device
     if workspace is None:
@@ -181,6 +191,41 @@ def kd_loss_fwd_bwd(h_t, W_t, h_s, W_s, mask=None, tau=1.0, kind=FKL, beta=0.5, 
         grad_W_s = torch.empty_like(W_s, dtype=tdt)
     kd_loss_fwd_bwd_raw(p, h_t, W_t, h_s, W_s, mask, loss, ptl, grad_h, grad_W_s, workspace)
     return dict(loss=loss, per_token_loss=ptl, grad_h_s=grad_h, grad_W_s=grad_W_s, workspace=workspace)
+
+
+def kd_loss_fwd_bwd_multi(h_ts, W_ts, weights, h_s, W_s, mask=None, tau=1.0, kind=FKL, beta=0.5, flags=0,
+                          grad_dtype=None):
+    """Multi-teacher call: lists of teacher hidden states / heads ([V,H] order) and weights."""
+    import torch
+    n = len(h_ts)
+    in_dtype = BF16 if h_s.dtype == torch.bfloat16 else F32
+    T, H_s = h_s.shape
+    V = W_s.shape[0]
+    if grad_dtype is None:
+        grad_dtype = in_dtype
+    p = make_params(T, h_ts[0].shape[1], H_s, V, kind, tau, beta, in_dtype, grad_dtype, W_VH, False, flags)
+    H_t = (ctypes.c_int64 * n)(*[int(h.shape[1]) for h in h_ts])
+    nbytes = ctypes.c_size_t(0)
+    st = lib().kd_loss_workspace_size_multi(ctypes.byref(p), n, H_t, ctypes.byref(nbytes))
+    if st != KD_OK:
+        raise KdLossError(st)
+    dev = h_s.device
+    ws = torch.empty((nbytes.value + 255) // 256 * 256, dtype=torch.uint8, device=dev)
+    tdt = torch.bfloat16 if grad_dtype == BF16 else torch.float32
+    loss = torch.empty(1, dtype=torch.float32, device=dev)
+    ptl = torch.empty(T, dtype=torch.float32, device=dev)
+    grad_h = torch.empty((T, H_s), dtype=tdt, device=dev)
+    grad_W = torch.empty_like(W_s, dtype=tdt)
+    hp = (ctypes.c_void_p * n)(*[h.data_ptr() for h in h_ts])
+    wp = (ctypes.c_void_p * n)(*[w.data_ptr() for w in W_ts])
+    wt = (ctypes.c_float * n)(*[float(w) for w in weights])
+    st = lib().kd_loss_fwd_bwd_multi(ctypes.byref(p), n, hp, wp, H_t, wt, _ptr(h_s), _ptr(W_s), _ptr(mask),
+                                     _ptr(loss), _ptr(ptl), _ptr(grad_h), _ptr(grad_W), _ptr(ws),
+                                     ctypes.c_size_t(ws.numel()),
+                                     ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    if st != KD_OK:
+        raise KdLossError(st)
+    return dict(loss=loss, per_token_loss=ptl, grad_h_s=grad_h, grad_W_s=grad_W)
 
 
 def kd_loss_fwd(h_t, W_t, h_s, W_s, mask=None, tau=1.0, kind=FKL, beta=0.5, w_layout=W_VH, workspace=None):

@@ -35,6 +35,8 @@ def test_ragged_multi_tile(name, kind, beta, monkeypatch):
 @pytest.mark.parametrize("tau", [0.7, 2.0])
 @pytest.mark.parametrize("name,kind,beta", KINDS[:3])
 def test_temperature(name, kind, beta, tau):
+    # V = 1000 leaves a ragged last vocabulary tile (104 rows): with tau > log2(e) the masked rows of
+    # that tile once produced infinities in lanes that saw no valid row
     cfg = I.scaled(I.workload(name), batch=2, seq=150, H_t=128, H_s=64, V=1000, tau=tau)
     data = I.generate(cfg)
     G.check(G.run_gpu(cfg, data), G.run_oracle(cfg, data), f"{name} tau={tau}")
@@ -155,3 +157,42 @@ def test_heavy_masks_are_compacted_correctly(keep):
     G.check(out, G.run_oracle(cfg, data), f"keep={keep}")
     ptl = G.to_host(out["per_token_loss"]); gh = G.to_host(out["grad_h_s"])
     assert (ptl[mask == 0] == 0).all() and (gh[mask == 0] == 0).all()
+
+
+def test_multi_teacher_and_tau2():
+    import torch
+    from oracle import kd_oracle as O
+    from paper_2603_01875_amd import kdloss as K
+    cfg = I.scaled(I.workload("fkl_bf16"), batch=2, seq=150, H_t=192, H_s=128, V=1544, tau=1.5)
+    cfg2 = I.scaled(I.workload("rkl_bf16"), batch=2, seq=150, H_t=320, H_s=128, V=1544, tau=1.5, seed=77)
+    d1 = I.generate(cfg); d2 = I.generate(cfg2)
+    weights = (0.25, 0.75)
+    for kind, beta in ((I.FKL, 0.5), (I.JSD, 0.3)):
+        ref = O.kd_loss_multi([d1["h_t"], d2["h_t"]], [d1["W_t"], d2["W_t"]], weights, d1["h_s"], d1["W_s"],
+                              d1["mask"], cfg.tau, kind, beta, O.W_VH)
+        ref["per_token_loss"] = ref["per_token_loss"] * (d1["mask"] != 0)
+        dev = lambda x: G.to_device(x, I.BF16)
+        out = K.kd_loss_fwd_bwd_multi([dev(d1["h_t"]), dev(d2["h_t"])], [dev(d1["W_t"]), dev(d2["W_t"])], weights,
+                                      dev(d1["h_s"]), dev(d1["W_s"]), torch.from_numpy(d1["mask"]).cuda(),
+                                      tau=cfg.tau, kind=kind, beta=beta)
+        torch.cuda.synchronize()
+        G.check(out, ref, f"multi kind={kind}")
+    # tau^2 flag on the single-teacher entry point
+    a = G.run_gpu(cfg, d1)
+    b = G.run_gpu(cfg, d1, flags=K.FLAG_TAU2)
+    assert float(b["loss"].item()) == pytest.approx(cfg.tau ** 2 * float(a["loss"].item()), rel=1e-6)
+    ref = O.kd_loss_fwd_bwd(d1["h_t"], d1["W_t"], d1["h_s"], d1["W_s"], d1["mask"], cfg.tau, cfg.kind, cfg.beta,
+                            O.W_VH, tau2=True)
+    ref["per_token_loss"] = ref["per_token_loss"] * (d1["mask"] != 0)
+    G.check(b, ref, "tau^2")
+
+
+@pytest.mark.parametrize("tau", [1.5, 4.0])
+@pytest.mark.parametrize("kind,beta", [(I.FKL, 0.5), (I.RKL, 0.5), (I.JSD, 0.4), (I.TVD, 0.5)])
+def test_ragged_last_tile_with_high_temperature(kind, beta, tau):
+    # regression: V % 128 = 8 leaves whole waves of the last tile without a valid vocabulary row; their
+    # running maximum must not follow the masked logits (it did when log2(e)/tau < 1 -> inf * 0 = nan)
+    cfg = I.scaled(I.workload("fkl_bf16"), batch=1, seq=300, H_t=128, H_s=64, V=1288, kind=kind, beta=beta, tau=tau)
+    data = I.generate(cfg)
+    extra = G.tvd_tie_allowance(cfg, data) if kind == I.TVD else None
+    G.check(G.run_gpu(cfg, data), G.run_oracle(cfg, data), f"kind={kind} tau={tau}", extra)

@@ -288,3 +288,31 @@ def test_planted_mistakes_are_caught():
     M = 0.8 * pt + 0.2 * ps                                        # weights on the wrong side
     wrong = 0.8 * sps.rel_entr(pt, M).sum(1) + 0.2 * sps.rel_entr(ps, M).sum(1)
     assert np.abs(l - wrong).max() > 1e-3
+
+
+# ---- multi-teacher and tau^2 conventions (defined by linearity; checked by finite differences) ------
+def _multi_loss(ps_, h_s, W_s, mask, tau, kind, beta, weights):
+    return sum(w * O.kd_loss_fwd_bwd(p["h_t"], p["W_t"], h_s, W_s, mask, tau, kind, beta)["loss"]
+               for w, p in zip(weights, ps_))
+
+
+def test_multi_teacher_gradient_is_gradient_of_weighted_sum():
+    rng = np.random.default_rng(31)
+    teachers = [dict(h_t=rng.standard_normal((3, 5)), W_t=0.7 * rng.standard_normal((5, 13))),
+                dict(h_t=rng.standard_normal((3, 8)), W_t=0.4 * rng.standard_normal((8, 13)))]
+    h_s = rng.standard_normal((3, 4)); W_s = 0.5 * rng.standard_normal((4, 13))
+    mask = np.array([1, 0, 1], np.uint8); w = (0.3, 1.7)
+    r = O.kd_loss_multi([t["h_t"] for t in teachers], [t["W_t"] for t in teachers], w, h_s, W_s, mask, 1.4, O.JSD, 0.3)
+    assert r["loss"] == pytest.approx(_multi_loss(teachers, h_s, W_s, mask, 1.4, O.JSD, 0.3, w), abs=1e-15)
+    eps = 1e-6
+    fd = np.zeros_like(W_s)
+    for i in np.ndindex(*W_s.shape):
+        up = W_s.copy(); up[i] += eps; dn = W_s.copy(); dn[i] -= eps
+        fd[i] = (_multi_loss(teachers, h_s, up, mask, 1.4, O.JSD, 0.3, w) -
+                 _multi_loss(teachers, h_s, dn, mask, 1.4, O.JSD, 0.3, w)) / (2 * eps)
+    assert np.abs(fd - r["grad_W_s"]).max() < 2e-9
+    # tau^2 convention: exactly tau^2 times everything
+    a = O.kd_loss_fwd_bwd(teachers[0]["h_t"], teachers[0]["W_t"], h_s, W_s, mask, 1.4, O.FKL)
+    b = O.kd_loss_fwd_bwd(teachers[0]["h_t"], teachers[0]["W_t"], h_s, W_s, mask, 1.4, O.FKL, tau2=True)
+    assert b["loss"] == pytest.approx(1.96 * a["loss"], rel=1e-14)
+    assert np.allclose(b["grad_h_s"], 1.96 * a["grad_h_s"], rtol=1e-13, atol=0)
