@@ -253,19 +253,21 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
   // Order inside one sub-step: fragment reads first (two per MFMA), then one load per MFMA.
   auto schedule_substep = [&]() {
     constexpr int n_mfma = MI * NI, n_ds = MI + NI;
-    constexpr int ds_slots = (n_ds + 1) / 2;
-    static_assert(ds_slots + LPS <= n_mfma, "not enough MFMAs to cover the memory instructions");
+    constexpr int ds_slots = (n_ds + 1) / 2 < n_mfma ? (n_ds + 1) / 2 : n_mfma - 1;
+    constexpr int vm_slots = n_mfma - ds_slots < LPS ? n_mfma - ds_slots : (LPS > 0 ? LPS : 1);
+    constexpr int vm_per = (LPS + vm_slots - 1) / vm_slots;
 #pragma unroll
     for (int i = 0; i < ds_slots; ++i) {
       __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(SG_DSREAD, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(SG_DSREAD, (n_ds + ds_slots - 1) / ds_slots, 0);
     }
 #pragma unroll
-    for (int i = 0; i < LPS; ++i) {
+    for (int i = 0; i < vm_slots; ++i) {
       __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(SG_VMEM, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(SG_VMEM, vm_per, 0);
     }
-    __builtin_amdgcn_sched_group_barrier(SG_MFMA, n_mfma - ds_slots - LPS, 0);
+    if (n_mfma - ds_slots - vm_slots > 0)
+      __builtin_amdgcn_sched_group_barrier(SG_MFMA, n_mfma - ds_slots - vm_slots, 0);
     __builtin_amdgcn_sched_barrier(0);
   };
 
