@@ -59,12 +59,11 @@ def main():
     import torch
     from paper_2603_01875_amd import inputs as I
     from paper_2603_01875_amd import kdloss as K
-    from tests.gpu_util import to_device
 
     torch.cuda.set_device(0)
     cfg = I.workload(args.workload)
     data = I.generate(cfg)
-    dev = {k: to_device(data[k], cfg.dtype) for k in ("h_t", "W_t", "h_s", "W_s")}
+    dev = {k: I.to_device(data[k], cfg.dtype) for k in ("h_t", "W_t", "h_s", "W_s")}
     mask = torch.from_numpy(data["mask"]).cuda()
     T, V, H_t, H_s = cfg.T, cfg.V, cfg.H_t, cfg.H_s
 

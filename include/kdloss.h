@@ -87,9 +87,11 @@ typedef struct {
 } kd_loss_params;
 
 /* Bytes of device workspace kd_loss_fwd_bwd needs for these parameters.
- * Host only.  The size is O(T * V_c + H_s * V_c + T * H_s) for a vocabulary
- * chunk V_c chosen by the library (a few thousand columns): it never grows
- * like T * V.  Returns KD_OK or the status kd_loss_fwd_bwd would return for
+ * Host only.  The size is O(T * V_c + H_s * V_c + T * (H_t + H_s)) for a vocabulary
+ * chunk V_c chosen by the library (a few thousand columns) - staging of dL/dz_s,
+ * fp32 sums of grad_h_s, compacted copies of the hidden states - plus copies of
+ * the heads only when they must be re-packed (fp32 inputs, hidden sizes that are
+ * not multiples of 64).  It never grows like T * V.  Returns KD_OK or the status kd_loss_fwd_bwd would return for
  * the same params. */
 kd_status kd_loss_workspace_size(const kd_loss_params* params, size_t* bytes);
 

@@ -132,3 +132,12 @@ def generate(cfg: KDConfig):
 def scaled(cfg: KDConfig, **kw) -> KDConfig:
     """Same recipe at other sizes (for parity cases the oracle finishes quickly)."""
     return dataclasses.replace(cfg, **kw)
+
+
+def to_device(x: np.ndarray, dtype: int, device="cuda"):
+    """Upload an array made by `generate` as a torch tensor of the storage dtype (bit-exact)."""
+    import torch
+    if dtype == BF16:
+        bits = bf16_bits(x)
+        return torch.from_numpy(bits.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(device)

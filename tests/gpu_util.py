@@ -9,12 +9,7 @@ LOSS_RTOL = 1e-3          # loss relative error
 GRAD_TOL = 2e-2           # gradient max-abs error, as a fraction of the oracle's max-abs value
 
 
-def to_device(x, dtype):
-    import torch
-    if dtype == I.BF16:
-        bits = I.bf16_bits(x)
-        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
-    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
+to_device = I.to_device
 
 
 def to_host(t):

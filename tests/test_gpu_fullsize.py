@@ -20,19 +20,66 @@ def test_medium_problem_full_oracle(name):
 
 
 def _sampled_rows_check(cfg, data, out, rows):
+    """Per-token loss and grad_h_s rows of the sampled tokens, computed by the oracle row by row
+    (the vocabulary axis is walked in chunks only to bound the fp64 copies of the heads)."""
     n = float(data["mask"].sum())
-    Wt = data["W_t"].astype(np.float64); Ws = data["W_s"].astype(np.float64)
-    z_t = data["h_t"][rows].astype(np.float64) @ Wt.T
-    z_s = data["h_s"][rows].astype(np.float64) @ Ws.T
+    ht = data["h_t"][rows].astype(np.float64); hs = data["h_s"][rows].astype(np.float64)
+    z_t = np.empty((len(rows), cfg.V)); z_s = np.empty((len(rows), cfg.V))
+    for v0 in range(0, cfg.V, 16384):
+        z_t[:, v0:v0 + 16384] = ht @ data["W_t"][v0:v0 + 16384].astype(np.float64).T
+        z_s[:, v0:v0 + 16384] = hs @ data["W_s"][v0:v0 + 16384].astype(np.float64).T
     l, g = O.divergence_rows(z_t, z_s, cfg.tau, cfg.kind, cfg.beta)
     ptl = G.to_host(out["per_token_loss"])[rows]
     l = l * (data["mask"][rows] != 0)              # masked tokens are reported as 0
     assert np.abs(ptl - l).max() <= 1e-3 * np.abs(l).max()
     dz = (data["mask"][rows].astype(np.float64) / (n * cfg.tau))[:, None] * g
-    gh_ref = dz @ Ws
-    gh = G.to_host(out["grad_h_s"])[rows]
+    gh_ref = np.zeros((len(rows), cfg.H_s))
+    for v0 in range(0, cfg.V, 16384):
+        gh_ref += dz[:, v0:v0 + 16384] @ data["W_s"][v0:v0 + 16384].astype(np.float64)
+    gh = G.to_host(out["grad_h_s"][torch_index(rows)])
     assert np.abs(gh - gh_ref).max() <= G.GRAD_TOL * np.abs(gh_ref).max()
     return l
+
+
+def torch_index(rows):
+    import torch
+    return torch.from_numpy(np.asarray(rows, dtype=np.int64)).cuda()
+
+
+def _properties(cfg, data, out):
+    """Checks that hold at any size (see the headline test for what each one pins)."""
+    import torch
+    mask = data["mask"].astype(bool)
+    ptl = out["per_token_loss"].double().cpu().numpy()
+    loss = float(out["loss"].item())
+    assert abs(loss - ptl[mask].mean()) <= 1e-5 * abs(loss)
+    gh = out["grad_h_s"]
+    if (~mask).any():
+        assert not gh[torch.from_numpy(~mask).cuda()].any()
+    gW = out["grad_W_s"]
+    scale = gW.abs().max().item()
+    colsum = gW.sum(dim=0, dtype=torch.float32).abs().max().item()
+    assert colsum <= 2e-2 * scale * np.sqrt(cfg.V)
+    h_s = G.to_device(data["h_s"], cfg.dtype); W_s = G.to_device(data["W_s"], cfg.dtype)
+    a = torch.dot(gh.flatten().double(), h_s.flatten().double()).item()
+    b = sum(torch.dot(gW[v0:v0 + 32768].flatten().double(), W_s[v0:v0 + 32768].flatten().double()).item()
+            for v0 in range(0, cfg.V, 32768))
+    assert abs(a - b) <= 2e-2 * max(abs(a), abs(b))
+    assert torch.isfinite(gW[-1]).all() and gW[-1].abs().max().item() > 0
+
+
+@pytest.mark.parametrize("name", ["large_teacher", "long_peaked"])
+def test_other_full_size_workloads(name):
+    """The two largest benchmark shapes at full size: sampled rows against the oracle + properties."""
+    cfg = I.workload(name)
+    data = I.generate(cfg)
+    out = G.run_gpu(cfg, data)
+    mask = data["mask"].astype(bool)
+    rows = np.array([0, 255, 256, cfg.T // 2 + 1, cfg.T - 1] + list(np.flatnonzero(~mask)[:2]))
+    l = _sampled_rows_check(cfg, data, out, rows)
+    if name == "long_peaked":        # near one-hot teacher: JSD_0.1 stays below its bound H(0.1)
+        assert (l <= 0.3251 + 1e-6).all() and np.isfinite(G.to_host(out["per_token_loss"])).all()
+    _properties(cfg, data, out)
 
 
 def test_headline_workload_sampled_outputs_and_properties():
