@@ -14,7 +14,7 @@ inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 struct Layout {
-  size_t meta, rowmap, inv, rowinfo, row_loss, partials, h_sT, W_sT, dz, dzT, gh32, total;
+  size_t meta, rowmap, inv, rowinfo, row_loss, partials, h_sT, dz, gh32, total;
   size_t prep_h_t, prep_W_t, prep_h_s, prep_W_s;   // re-packed operands (only when needed)
 };
 
@@ -107,12 +107,10 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward) {
   if (q.prep_Ws) L.prep_W_s = take((size_t)q.V * q.K_s * 2);
   if (with_backward) {
     L.h_sT = take((size_t)q.H_s * q.T_pad * 2);
-    L.W_sT = take((size_t)q.H_s * q.V_c * 2);
     L.dz = take((size_t)q.T_pad * q.V_c * 2);
-    L.dzT = take((size_t)q.V_c * q.T_pad * 2);
     L.gh32 = take((size_t)q.n_ksplit_h * q.T * q.H_s * 4);
   } else {
-    L.h_sT = L.W_sT = L.dz = L.dzT = L.gh32 = off;
+    L.h_sT = L.dz = L.gh32 = off;
   }
   // the only buffers whose size depends on the teacher come last, so that everything above sits at
   // the same offsets for every teacher of a multi-teacher call
@@ -130,9 +128,7 @@ void carve(Problem& q, const Layout& L, void* ws) {
   q.row_loss = reinterpret_cast<float*>(b + L.row_loss);
   q.partials = reinterpret_cast<float*>(b + L.partials);
   q.h_sT = b + L.h_sT;
-  q.W_sT = b + L.W_sT;
   q.dz = b + L.dz;
-  q.dzT = b + L.dzT;
   q.gh32 = reinterpret_cast<float*>(b + L.gh32);
   q.user_h_t = q.h_t; q.user_W_t = q.W_t; q.user_h_s = q.h_s; q.user_W_s = q.W_s;
   // without a mask the hidden states are used in place unless they need re-packing anyway
@@ -229,12 +225,10 @@ kd_status run_backward(const Problem& q, hipStream_t st, bool first_teacher, boo
       ProfileScope ps(KD_PROF_GRAD, st);
       KD_TRY(kd::launch_grad_chunk(q, (int)v0, width, st));
     }
-    // W_s[chunk]^T [H_s][V_c]: the K-contiguous operand of grad_h_s
-    KD_TRY(kd::launch_transpose(static_cast<const char*>(q.W_s) + (size_t)v0 * q.K_s * 2, q.K_s, width, q.H_s,
-                                q.W_sT, q.V_c, (int)round_up(width, 64), st));
-    kd::GemmDesc gw{};   // grad_W_s[v][h] = sum_t h_sT[h][t] dzT[v][t]
+    kd::GemmDesc gw{};   // grad_W_s[v][h] = sum_t h_sT[h][t] dz[t][v]   (dz read token-major as it lies)
     gw.A = q.h_sT; gw.lda = q.T_pad; gw.M = q.H_s;
-    gw.B = q.dzT; gw.ldb = q.T_pad; gw.N = width;
+    gw.B = q.dz; gw.ldb = q.V_c; gw.N = width;
+    gw.k_major = 2; gw.k_rows = q.T_pad;
     gw.K = q.T_pad; gw.k_per_split = 0;
     gw.meta = q.meta; gw.k_from_meta = 1;        // only the token tiles that hold valid tokens
     gw.out = static_cast<char*>(q.grad_W_s) + (size_t)v0 * q.H_s * gsz;
@@ -244,8 +238,10 @@ kd_status run_backward(const Problem& q, hipStream_t st, bool first_teacher, boo
       ProfileScope ps(KD_PROF_GEMM_GRAD_W, st);
       KD_TRY(kd::launch_gemm(gw, q.n_cu, st));
     }
-    kd::GemmDesc gh{};   // grad_h_s[t][h] += sum_v W_sT[h][v] dz[t][v]
-    gh.A = q.W_sT; gh.lda = q.V_c; gh.M = q.H_s;
+    kd::GemmDesc gh{};   // grad_h_s[t][h] += sum_v W_s[v][h] dz[t][v]   (the head read vocabulary-major as it lies;
+                         // dz is zero from the chunk's last valid column to the end of its 128-column tile)
+    gh.A = static_cast<const char*>(q.W_s) + (size_t)v0 * q.K_s * 2; gh.lda = q.K_s; gh.M = q.H_s;
+    gh.k_major = 1; gh.k_rows = width;
     gh.B = q.dz; gh.ldb = q.V_c; gh.N = q.T;
     gh.meta = q.meta; gh.n_from_meta = 1;        // rows = valid tokens
     gh.K = (int)round_up(width, 64); gh.k_per_split = q.ksteps_h * 64;

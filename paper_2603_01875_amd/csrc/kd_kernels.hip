@@ -6,8 +6,10 @@
 //   rows     : (JSD, TVD, skewed KL) logit tiles again -> two row sums per token (RowTerm)
 //   finalize : n = sum mask, loss, per-row gradient scale mask/(n tau)
 //   per vocabulary chunk:
-//     grad   : logit tiles again -> dL/dz_s tile in bf16, stored both [T,Vc] and [Vc,T]
+//     grad   : logit tiles again -> dL/dz_s tile in bf16, stored once as [T,Vc]
 //     gemm   : grad_W_s[chunk] = dz^T . h_s     and     grad_h_s += dz . W_s[chunk]
+//              (dz in the first and W_s in the second are contracted over their OUTER index:
+//              they are read as they lie, through the k-major operand path of tile_loop)
 //   gradh_finish : fp32 partial sums -> grad_h_s
 // All logarithms inside the kernels are base 2: a = z * log2(e)/tau.
 #include "kd_mfma.hpp"
@@ -18,7 +20,8 @@
 #define KD_LOGIT_CFG 2, 2, 4, 64, 3     // MI, NI, WN, BK, NST: 128 x 256 tile, 8 waves
 #endif
 #ifndef KD_GEMM_CFG
-#define KD_GEMM_CFG 2, 4, 2, 64, 3      // 128 x 256 tile, 4 waves
+#define KD_GEMM_CFG 2, 2, 4, 64, 3      // 128 x 256 tile, 8 waves (the second wave per SIMD hides the
+                                        // bursts of transposing LDS reads of the k-major operand)
 #endif
 
 namespace kd {
@@ -71,7 +74,6 @@ struct LogitArgs {
   float* partials;     // stats: [n_split*4][5][T_pad];  jsd: [n_split*4][2][T_pad]
   const f32x4* rowinfo;// [T_pad]: {lse2_t, lse2_s, mask/(n tau), row term}
   bf16_t* dz;          // [T_pad][ldz]   chunk of dL/dz_s, vocabulary contiguous
-  bf16_t* dzT;         // [Vc][T_pad]    the same chunk, token contiguous
   int ldz;
 };
 
@@ -363,7 +365,6 @@ struct GradEpi {
             }
             const float d = ok ? s * g : 0.f;
             o[i] = (bf16_t)d;
-            a.dzT[(int64_t)(mloc0 + m + i) * a.T_pad + n] = o[i];
           }
           *(bf16x4*)(a.dz + (int64_t)n * a.ldz + mloc0 + m) = o;
         }
@@ -421,8 +422,11 @@ struct GemmArgs {
   const int* meta;     // device-side plan (may be null when neither flag below is set)
   int n_from_meta;     // N = number of valid tokens (rows of the compacted B operand)
   int k_from_meta;     // K = valid tokens rounded up to whole token tiles
+  int k_rows;          // k-major operand: k-rows that exist in memory (rows beyond are clamped)
 };
 
+// KM: which operand is stored k-major (1: A[k][m], 2: B[k][n]); the other one is K-contiguous.
+template <int KM>
 struct GemmWork {
   const GemmArgs& a;
   int L, G, n_tiles, N, K, n_nt, bb;
@@ -447,8 +451,9 @@ struct GemmWork {
     block_decode(q - ks * per_split, a.n_mt, a.ba, bb, mt, nt);
     const int k0 = ks * a.ksteps * GCfg::BK;
     WorkItem it;
-    it.A0 = it.A1 = a.A + (int64_t)mt * GCfg::BM * a.lda + k0;
-    it.B0 = it.B1 = a.B + (int64_t)nt * BN * a.ldb + k0;
+    it.A0 = it.A1 = (KM & 1) ? a.A + (int64_t)k0 * a.lda + mt * GCfg::BM : a.A + (int64_t)mt * GCfg::BM * a.lda + k0;
+    it.B0 = it.B1 = (KM & 2) ? a.B + (int64_t)k0 * a.ldb + nt * BN : a.B + (int64_t)nt * BN * a.ldb + k0;
+    it.ka_rows = it.kb_rows = a.k_rows - k0;
     it.a_rows = min(GCfg::BM, a.M - mt * GCfg::BM);
     it.b_rows = min(BN, N - nt * BN);
     it.nk0 = it.nk1 = a.k_from_meta ? K / GCfg::BK : min(a.ksteps, K / GCfg::BK - ks * a.ksteps);
@@ -502,11 +507,12 @@ struct StoreEpi {
   }
 };
 
+template <int KM>
 KD_GEMM_KERNEL void gemm_kernel(const GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  GemmWork work(a);
+  GemmWork<KM> work(a);
   StoreEpi epi(a);
-  tile_loop<1, GCfg>(work, epi, a.lda, a.lda, a.ldb, a.ldb, smem);
+  tile_loop<1, GCfg, KM>(work, epi, a.lda, a.lda, a.ldb, a.ldb, smem);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -815,7 +821,7 @@ hipError_t launch_grad_chunk(const Problem& p, int v0, int width, hipStream_t st
   a.vt0 = v0 / BM;
   a.n_vt = (width + BM - 1) / BM;
   a.bb = largest_divisor_le(a.n_vt, 8);
-  a.dz = (bf16_t*)p.dz; a.dzT = (bf16_t*)p.dzT; a.ldz = p.V_c;
+  a.dz = (bf16_t*)p.dz; a.ldz = p.V_c;
   const int tiles = p.n_tt * a.n_vt;
   int grid = tiles < p.n_cu ? tiles : p.n_cu;
   switch (p.kind) {
@@ -850,9 +856,12 @@ hipError_t launch_gemm(const GemmDesc& d, int n_cu, hipStream_t st) {
   a.ba = largest_divisor_le(a.n_mt, 8);
   a.bb = largest_divisor_le(a.n_nt, 4);
   a.meta = d.meta; a.n_from_meta = d.n_from_meta; a.k_from_meta = d.k_from_meta;
+  a.k_rows = d.k_rows;
   const int tiles = a.n_mt * a.n_nt * a.n_ksplit;       // worst case (no token masked)
   const int grid = tiles < n_cu ? tiles : n_cu;
-  return launch_big(gemm_kernel, grid, GCfg::NT, GCfg::SMEM_BYTES, st, &a);
+  if (d.k_major == 1) return launch_big(gemm_kernel<1>, grid, GCfg::NT, GCfg::SMEM_BYTES, st, &a);
+  if (d.k_major == 2) return launch_big(gemm_kernel<2>, grid, GCfg::NT, GCfg::SMEM_BYTES, st, &a);
+  return hipErrorInvalidValue;
 }
 
 hipError_t launch_prepare(const void* src, int src_f32, int R, int H, void* dst, int K, int split_mode,

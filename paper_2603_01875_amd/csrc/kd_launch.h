@@ -42,9 +42,7 @@ struct Problem {
   float* row_loss;     // [T_pad]
   float* partials;     // [n_split*4][5][T_pad]
   void* h_sT;          // bf16 [H_s][T_pad]
-  void* W_sT;          // bf16 [H_s][V_c]
   void* dz;            // bf16 [T_pad][V_c]
-  void* dzT;           // bf16 [V_c][T_pad]
   float* gh32;         // [n_ksplit_h][T][H_s]
 };
 
@@ -61,6 +59,9 @@ struct GemmDesc {
   const int* meta;        // device-side plan, needed when a flag below is set
   int n_from_meta;        // N = number of valid tokens
   int k_from_meta;        // K = valid tokens rounded up to whole token tiles (no split-K)
+  int k_major;            // 1: A is stored [K][M] (element (m, k) at A[k * lda + m]); 2: B is stored [K][N]
+  int k_rows;             // rows of the k-major operand that exist; K may round up beyond, the other
+                          // operand must be zero there
 };
 
 hipError_t launch_rowmap(const Problem& p, hipStream_t st);

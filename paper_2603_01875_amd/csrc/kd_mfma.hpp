@@ -96,6 +96,7 @@ struct WorkItem {
   const bf16_t *B0, *B1;   // first row of the tile in B
   int a_rows;              // valid rows of A in this tile (1..BM); rows beyond are clamped
   int b_rows;              // valid rows of B in this tile (1..BN)
+  int ka_rows, kb_rows;    // k-major operands only: k-rows that exist from the item's k origin on
   int nk0, nk1;            // k-steps of BK elements per phase (>= 1 for phases in use)
   int m0, n0;              // tile origin, passed through to the epilogue
   int aux;                 // free for the work map (e.g. split-K index)
@@ -138,7 +139,63 @@ typedef __attribute__((address_space(3))) void lds_void_t;
 // sched_group_barrier masks
 constexpr int SG_MFMA = 0x008, SG_VMEM = 0x010, SG_DSREAD = 0x100;
 
-template <int NPHASE, class Cfg, class Work, class Epi>
+//
+// k-major operands (KM bit 0: A, bit 1: B).  An operand may instead be stored with the
+// contraction index outermost: element (row r, k) at P[k * ld + r], P pointing at (k origin,
+// first row of the tile).  Its LDS tile is then [BK][R] (R = BM or BN rows, contiguous), the
+// 16-byte chunks of a k-row permuted by XOR with 4 (k mod 4), and a fragment is fetched by
+// two transposing reads (ds_read_b64_tr_b16): in every group of 16 lanes, lane i receives as
+// element j the (i mod 4)-th of the four values addressed by lane i/4 + 4j, so lane i
+// addresses k-row i/4 (+4 for the second read), rows 4 (i mod 4) .. +3 of its group's 16.
+// The four k-rows that half a wave reads at once then fall into four different 64-byte
+// bank groups.  Chunks past the valid rows and k-rows past ka_rows / kb_rows are clamped to
+// the last valid one (the other operand must be zero there).
+//
+// The transposing reads are written as inline assembly with hand-placed waits: issued through
+// the compiler's builtin, every one of them is preceded by a wait for ALL outstanding direct
+// loads (the compiler cannot tell that they target another LDS stage), which serialises the
+// pipeline.  A k-major fragment therefore lives in two register pairs that the hardware fills
+// asynchronously; km_wait() ties them to an "s_waitcnt lgkmcnt(0)" placed at the top of the
+// sub-step that consumes them (their reads were issued one sub-step earlier), and only the
+// values that leave km_wait() are ever used.
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
+
+struct KmFrag { s16x4 lo, hi; };
+template <bool KMAJOR> struct FragT { typedef bf16x8 type; };
+template <> struct FragT<true> { typedef KmFrag type; };
+
+__device__ __forceinline__ bf16x8 frag_op(const bf16x8& f) { return f; }
+__device__ __forceinline__ bf16x8 frag_op(const KmFrag& f) {
+  const s16x8 v = __builtin_shufflevector(f.lo, f.hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+// k-rows k and k+4 of one fragment: OFF = byte offset of k-row k from addr, ROWB4 = 4 k-rows
+template <int OFF, int ROWB4>
+__device__ __forceinline__ void km_read(KmFrag& f, uint32_t addr) {
+  static_assert(OFF >= 0 && OFF + ROWB4 < 65536, "ds offset field");
+  asm volatile("ds_read_b64_tr_b16 %0, %2 offset:%3\n\tds_read_b64_tr_b16 %1, %2 offset:%4"
+               : "=&v"(f.lo), "=&v"(f.hi)
+               : "v"(addr), "n"(OFF), "n"(OFF + ROWB4));
+}
+template <int N>
+__device__ __forceinline__ void km_wait(KmFrag (&f)[N]) {
+#pragma unroll
+  for (int i = 0; i < N; ++i) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[i].lo), "+v"(f[i].hi));
+}
+template <int N>
+__device__ __forceinline__ void km_wait(bf16x8 (&)[N]) {}
+
+template <int V> struct IntC { static constexpr int value = V; };
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(IntC<I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+
+template <int NPHASE, class Cfg, int KM = 0, class Work, class Epi>
 __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
                                           const int lda0, const int lda1, const int ldb0, const int ldb1,
                                           char* smem) {
@@ -146,6 +203,11 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
   constexpr int A_LOADS = Cfg::A_LOADS, LOADS = Cfg::LOADS, LPS = Cfg::LOADS_PER_SUB;
   constexpr int A_STAGE_BYTES = Cfg::A_STAGE_BYTES, STAGE_BYTES = Cfg::STAGE_BYTES;
   constexpr int ROWB = Cfg::ROWB;
+  constexpr bool AKM = (KM & 1) != 0, BKM = (KM & 2) != 0;
+  constexpr int BK = Cfg::BK;
+  constexpr int CPR_A = Cfg::BM / 8, CPR_B = BN / 8;                 // chunks per k-row
+  constexpr int KPL_A = Cfg::NT / CPR_A, KPL_B = Cfg::NT / CPR_B;    // k-rows per load instruction
+  static_assert(KM == 0 || (KPL_A % 4 == 0 && KPL_B % 4 == 0 && BK % 16 == 0), "k-major swizzle");
   typedef typename Cfg::Acc Acc;
 
   const int tid = threadIdx.x;
@@ -167,17 +229,51 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
   bool more = true;
   WorkItem li = work.item(0);
   const char *l_pa, *l_pb;      // uniform: tile base + k offset, in bytes
+  int64_t l_step_a = ROWB, l_step_b = ROWB;   // bytes from one k-step to the next
   uint32_t loff[LOADS];         // per lane: byte offset of its 16 bytes inside the k-slab
+  const int kma_row = tid / CPR_A, kma_c = (tid % CPR_A) ^ (4 * (kma_row & 3));
+  const int kmb_row = tid / CPR_B, kmb_c = (tid % CPR_B) ^ (4 * (kmb_row & 3));
+  // offsets of the k-major operands for the k-step that starts k_done elements into the phase
+  auto km_offsets = [&](int k_done) {
+    if (AKM) {
+      const uint32_t la = (uint32_t)(l_phase ? lda1 : lda0);
+      const int clim = (li.a_rows + 7) / 8 - 1, rem = li.ka_rows - k_done - 1;
+      const int c = kma_c < clim ? kma_c : clim;
+#pragma unroll
+      for (int j = 0; j < A_LOADS; ++j) {
+        int kr = kma_row + KPL_A * j;
+        kr = kr < rem ? kr : rem;
+        kr = kr > 0 ? kr : 0;
+        loff[j] = ((uint32_t)kr * la + c * 8) * 2;
+      }
+    }
+    if (BKM) {
+      const uint32_t lb = (uint32_t)(l_phase ? ldb1 : ldb0);
+      const int clim = (li.b_rows + 7) / 8 - 1, rem = li.kb_rows - k_done - 1;
+      const int c = kmb_c < clim ? kmb_c : clim;
+#pragma unroll
+      for (int j = 0; j < Cfg::B_LOADS; ++j) {
+        int kr = kmb_row + KPL_B * j;
+        kr = kr < rem ? kr : rem;
+        kr = kr > 0 ? kr : 0;
+        loff[A_LOADS + j] = ((uint32_t)kr * lb + c * 8) * 2;
+      }
+    }
+  };
   auto set_cursor = [&]() {
     const uint32_t la = (uint32_t)(l_phase ? lda1 : lda0), lb = (uint32_t)(l_phase ? ldb1 : ldb0);
 #pragma unroll
     for (int j = 0; j < LOADS; ++j) {
       const bool isA = j < A_LOADS;
+      if (isA ? AKM : BKM) continue;
       int r = lrow + Cfg::ROWS_PER_LOAD * (isA ? j : j - A_LOADS);
       const int lim = isA ? li.a_rows : li.b_rows;
       r = r < lim ? r : lim - 1;
       loff[j] = ((uint32_t)r * (isA ? la : lb) + lchunk * 8) * 2;
     }
+    if (KM) km_offsets(0);
+    if (AKM) l_step_a = (int64_t)BK * 2 * la;
+    if (BKM) l_step_b = (int64_t)BK * 2 * lb;
     l_pa = (const char*)uniform(l_phase ? li.A1 : li.A0);
     l_pb = (const char*)uniform(l_phase ? li.B1 : li.B0);
     l_nk = l_phase ? li.nk1 : li.nk0;
@@ -193,8 +289,13 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
                                        (lds_void_t*)(sbase + j * (Cfg::NT * 16)), 16, 0, 0);
   };
   auto advance = [&]() {
-    l_pa += ROWB;
-    l_pb += ROWB;
+    l_pa += AKM ? l_step_a : ROWB;
+    l_pb += BKM ? l_step_b : ROWB;
+    if (KM && l_k + 1 < l_nk) {
+      // the k-step now under the cursor runs past the last k-row that exists: clamp its rows
+      const int k_end = (l_k + 2) * BK;
+      if ((AKM && k_end > li.ka_rows) || (BKM && k_end > li.kb_rows)) km_offsets((l_k + 1) * BK);
+    }
     if (++l_k == l_nk) {
       l_k = 0;
       if (NPHASE > 1 && l_phase == 0) {
@@ -213,8 +314,8 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
         l_item = n_items - 1;
         l_phase = NPHASE - 1;
         l_k = l_nk - 1;
-        l_pa -= ROWB;
-        l_pb -= ROWB;
+        l_pa -= AKM ? l_step_a : ROWB;
+        l_pb -= BKM ? l_step_b : ROWB;
       }
     }
   };
@@ -229,6 +330,22 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
   const int a_base = (wm * 32 * MI + frow) * ROWB;
   const int b_base = A_STAGE_BYTES + (wn * 32 * NI + frow) * ROWB;
 
+  // k-major fragments: byte offset of the lane's first transposing read of sub-step 0
+  int kma_f[MI], kmb_f[NI];
+  {
+    const int g = lane >> 4, r = lane & 15;
+    const int sw = 4 * (r >> 2), low = 2 * (g & 1) + ((r & 3) >> 1), kr = 8 * (g >> 1) + (r >> 2);
+#pragma unroll
+    for (int mt = 0; mt < MI; ++mt)
+      kma_f[mt] = kr * (2 * Cfg::BM) + ((((wm * 32 * MI + mt * 32) / 8) ^ sw) + low) * 16 + (r & 1) * 8;
+#pragma unroll
+    for (int nt = 0; nt < NI; ++nt)
+      kmb_f[nt] = A_STAGE_BYTES + kr * (2 * BN) + ((((wn * 32 * NI + nt * 32) / 8) ^ sw) + low) * 16 + (r & 1) * 8;
+  }
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_void_t*)smem;   // LDS byte address of stage 0
+  typedef typename FragT<AKM>::type AFrag;
+  typedef typename FragT<BKM>::type BFrag;
+
   Acc acc0, acc1;
   Cfg::zero(acc0);
   if (NPHASE > 1) Cfg::zero(acc1);
@@ -236,23 +353,37 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
   int stage = 0;            // LDS stage of the k-step being consumed
   int fill = NST - 1;       // LDS stage being refilled (released by the previous k-step)
 
-  auto read_frags = [&](int st, int ks, bf16x8 (&af)[MI], bf16x8 (&bfr)[NI]) {
+  auto read_frags = [&](int st, auto ks_c, AFrag (&af)[MI], BFrag (&bfr)[NI]) {
+    constexpr int ks = decltype(ks_c)::value;
     const char* base = smem + st * STAGE_BYTES;
+    const uint32_t lbase = lds0 + st * STAGE_BYTES;
 #pragma unroll
-    for (int mt = 0; mt < MI; ++mt) af[mt] = *(const bf16x8*)(base + a_base + mt * 32 * ROWB + fk[ks]);
+    for (int mt = 0; mt < MI; ++mt) {
+      if constexpr (AKM) km_read<ks * 16 * (2 * Cfg::BM), 4 * (2 * Cfg::BM)>(af[mt], lbase + kma_f[mt]);
+      else af[mt] = *(const bf16x8*)(base + a_base + mt * 32 * ROWB + fk[ks]);
+    }
 #pragma unroll
-    for (int nt = 0; nt < NI; ++nt) bfr[nt] = *(const bf16x8*)(base + b_base + nt * 32 * ROWB + fk[ks]);
+    for (int nt = 0; nt < NI; ++nt) {
+      if constexpr (BKM) km_read<ks * 16 * (2 * BN), 4 * (2 * BN)>(bfr[nt], lbase + kmb_f[nt]);
+      else bfr[nt] = *(const bf16x8*)(base + b_base + nt * 32 * ROWB + fk[ks]);
+    }
   };
-  auto mma = [&](Acc& acc, const bf16x8 (&af)[MI], const bf16x8 (&bfr)[NI]) {
+  // waits for the k-major fragments about to be multiplied (no-op for K-contiguous operands,
+  // whose reads the compiler tracks itself)
+  auto wait_frags = [&](AFrag (&af)[MI], BFrag (&bfr)[NI]) {
+    km_wait(af);
+    km_wait(bfr);
+  };
+  auto mma = [&](Acc& acc, const AFrag (&af)[MI], const BFrag (&bfr)[NI]) {
 #pragma unroll
     for (int mt = 0; mt < MI; ++mt)
 #pragma unroll
       for (int nt = 0; nt < NI; ++nt)
-        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mt], bfr[nt], acc[mt][nt], 0, 0, 0);
+        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_op(af[mt]), frag_op(bfr[nt]), acc[mt][nt], 0, 0, 0);
   };
   // Order inside one sub-step: fragment reads first (two per MFMA), then one load per MFMA.
   auto schedule_substep = [&]() {
-    constexpr int n_mfma = MI * NI, n_ds = MI + NI;
+    constexpr int n_mfma = MI * NI, n_ds = (AKM ? 0 : MI) + (BKM ? 0 : NI);   // reads the scheduler sees
     constexpr int ds_slots = (n_ds + 1) / 2 < n_mfma ? (n_ds + 1) / 2 : n_mfma - 1;
     constexpr int vm_slots = n_mfma - ds_slots < LPS ? n_mfma - ds_slots : (LPS > 0 ? LPS : 1);
     constexpr int vm_per = (LPS + vm_slots - 1) / vm_slots;
@@ -272,31 +403,36 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
   };
 
   // Fragments of sub-step 0 of the k-step about to be consumed; kept across k-steps.
-  bf16x8 fa0[MI], fb0[NI];
+  AFrag fa0[MI];
+  BFrag fb0[NI];
 
   // One k-step.  On entry fa0/fb0 hold sub-step 0.
   auto kstep = [&](Acc& acc) {
-    bf16x8 fa1[MI], fb1[NI];
+    AFrag fa1[MI];
+    BFrag fb1[NI];
     const int next = stage == NST - 1 ? 0 : stage + 1;
-#pragma unroll
-    for (int ks = 0; ks < KS - 1; ++ks) {
+    static_for<0, KS - 1>([&](auto ks_c) {
+      constexpr int ks = decltype(ks_c)::value;
       // even sub-steps multiply (fa0, fb0) and fetch into (fa1, fb1); odd ones the reverse
-      if (ks % 2 == 0) {
-        read_frags(stage, ks + 1, fa1, fb1);
+      if constexpr (ks % 2 == 0) {
+        wait_frags(fa0, fb0);
+        read_frags(stage, IntC<ks + 1>{}, fa1, fb1);
         issue_loads(fill, ks * LPS < LOADS ? ks * LPS : LOADS, (ks + 1) * LPS < LOADS ? (ks + 1) * LPS : LOADS);
         mma(acc, fa0, fb0);
       } else {
-        read_frags(stage, ks + 1, fa0, fb0);
+        wait_frags(fa1, fb1);
+        read_frags(stage, IntC<ks + 1>{}, fa0, fb0);
         issue_loads(fill, ks * LPS < LOADS ? ks * LPS : LOADS, (ks + 1) * LPS < LOADS ? (ks + 1) * LPS : LOADS);
         mma(acc, fa1, fb1);
       }
       schedule_substep();
-    }
+    });
     // k-step g+1 must have landed; after the barrier nobody reads stage `stage` any more
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(Cfg::WAIT_STEADY) : "memory");
     // last sub-step (KS-1, odd): multiplies (fa1, fb1), fetches sub-step 0 of the next k-step
+    wait_frags(fa1, fb1);
     issue_loads(fill, Cfg::LOADS_BEFORE_BARRIER, LOADS);
-    read_frags(next, 0, fa0, fb0);
+    read_frags(next, IntC<0>{}, fa0, fb0);
     mma(acc, fa1, fb1);
     schedule_substep();
     advance();
@@ -311,7 +447,7 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
     advance();
   }
   asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(Cfg::WAIT_PROLOGUE) : "memory");
-  read_frags(0, 0, fa0, fb0);
+  read_frags(0, IntC<0>{}, fa0, fb0);
 
   for (int c_item = 0; c_item < n_items; ++c_item) {
     const WorkItem ci = work.item(c_item);
