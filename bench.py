@@ -47,6 +47,9 @@ def main():
     ap.add_argument("--workload", default="fkl_bf16")
     ap.add_argument("--cpu-rows", type=int, default=64, help="tokens of the oracle sample (0 = skip)")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "traffic.json"))
+    ap.add_argument("--teacher-fp8", action="store_true",
+                    help="optional mode, not the headline: teacher hidden states and head quantised to e4m3 "
+                         "(one scale each) and the teacher logit tiles on the fp8 matrix pipe")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (scale for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -67,7 +70,15 @@ def main():
     mask = torch.from_numpy(data["mask"]).cuda()
     T, V, H_t, H_s = cfg.T, cfg.V, cfg.H_t, cfg.H_s
 
-    p = K.make_params(T, H_t, H_s, V, cfg.kind, cfg.tau, cfg.beta, K.BF16, K.BF16, K.W_VH)
+    flags, t_scale = 0, 0.0
+    if args.teacher_fp8:
+        # quantise once (the head is frozen; hidden states would be quantised per batch by one more small kernel)
+        s_h = float(dev["h_t"].abs().max().float().item()) / 448.0
+        s_W = float(dev["W_t"].abs().max().float().item()) / 448.0
+        dev["h_t"] = K.quantize_e4m3(dev["h_t"], s_h)
+        dev["W_t"] = K.quantize_e4m3(dev["W_t"], s_W)
+        flags, t_scale = K.FLAG_TEACHER_FP8, float(np.float32(s_h) * np.float32(s_W))
+    p = K.make_params(T, H_t, H_s, V, cfg.kind, cfg.tau, cfg.beta, K.BF16, K.BF16, K.W_VH, False, flags, t_scale)
     ws = K.alloc_workspace(p)
     vc, n_launch = K.kd_loss_plan_info(p)
     loss = torch.empty(1, dtype=torch.float32, device="cuda")
@@ -125,9 +136,12 @@ def main():
     flop_alg = n_valid * V * (2.0 * H_t + 6.0 * H_s)
     flop_exec = passes * logit_flop + 4.0 * T_comp * V * H_s
     stats_tflops = logit_flop / (stats_avg * 1e-3) / 1e12
+    # fp8 teacher: the student share of a launch runs against the bf16 peak, the teacher share against the
+    # fp8 peak (5 PFLOP/s); the launch's peak is the flop-weighted harmonic mean of the two
+    peak = (H_t + H_s) / (H_s / PEAK_BF16_TFLOPS + H_t / 5000.0) if args.teacher_fp8 else PEAK_BF16_TFLOPS
 
     traffic = None
-    if os.path.exists(args.traffic_file):
+    if os.path.exists(args.traffic_file) and not args.teacher_fp8:
         try:
             traffic = json.load(open(args.traffic_file)).get(args.workload, {}).get("stats_kernel_bytes")
         except Exception:
@@ -137,16 +151,17 @@ def main():
         "metric": METRIC, "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "bf16 (teacher operands e4m3)" if args.teacher_fp8 else "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "T": T, "H_t": H_t, "H_s": H_s, "V": V,
                    "kind": {0: "fkl", 1: "rkl", 2: "jsd", 3: "tvd", 4: "skew_fkl", 5: "skew_rkl"}[cfg.kind], "tau": cfg.tau, "beta": cfg.beta,
-                   "valid_tokens": n_valid, "computed_token_rows": T_comp, "w_layout": "VH", "vocab_chunk": vc, "launches_per_step": n_launch},
+                   "valid_tokens": n_valid, "computed_token_rows": T_comp, "w_layout": "VH", "teacher_fp8": bool(args.teacher_fp8), "vocab_chunk": vc, "launches_per_step": n_launch},
         "roofline": {"bound": "mfma", "kernel": "stats_kernel", "achieved": stats_tflops,
-                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": stats_tflops / PEAK_BF16_TFLOPS,
+                     "peak": peak, "unit": "TFLOP/s", "frac": stats_tflops / peak,
                      "traffic": traffic, "launch_ms": stats_avg, "flop_per_launch": logit_flop},
         "tflops_algorithmic": flop_alg / (ms_per_step * 1e-3) / 1e12,
         "tflops_executed": flop_exec / (ms_per_step * 1e-3) / 1e12,
-        "mfma_frac_whole_step": flop_exec / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "mfma_frac_whole_step": (flop_exec / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS if not args.teacher_fp8 else
+                                 (flop_exec - passes * 2.0 * T_comp * V * H_t / 2) / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS),
         "kernel_ms": dict(stats=stats_avg, **fam),
         "workspace_bytes": int(ws.numel()), "two_T_V_bytes": 2 * T * V,
         "loss": float(loss.item()),

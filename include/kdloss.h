@@ -68,7 +68,13 @@ typedef enum { KD_W_HV = 0, KD_W_VH = 1 } kd_wlayout;
 /* KD_FLAG_TAU2: multiply the loss, the per-token losses and both gradients by tau^2 (the
  * convention that keeps gradient magnitudes independent of the temperature).  Off by default:
  * the paper does not mention it. */
-typedef enum { KD_FLAG_TAU2 = 1 } kd_flags;
+/* KD_FLAG_TEACHER_FP8: h_t and W_t hold OCP e4m3 bytes (one per element) instead of in_dtype values,
+ * quantised with one scale per array (kd_quantize_e4m3):  z_t = teacher_scale * sum_k q_h[t,k] q_W[v,k],
+ * teacher_scale = scale_h * scale_W.  The teacher logit tiles then run on the fp8 matrix pipe at twice the
+ * bf16 rate and half the operand traffic; everything else (student side, divergence, gradients) is unchanged.
+ * An extension in the spirit of the paper's FP8 teacher inference (Table 3): the paper does not quantise the
+ * head.  Requires in_dtype == KD_BF16 and H_t a multiple of 128; not available in the multi-teacher call. */
+typedef enum { KD_FLAG_TAU2 = 1, KD_FLAG_TEACHER_FP8 = 2 } kd_flags;
 
 typedef struct {
   int64_t T;            /* tokens (batch x sequence, flattened)                     */
@@ -84,6 +90,8 @@ typedef struct {
   int32_t accumulate_grad_W; /* 0: grad_W_s is overwritten. 1: added to (gradient
                            accumulation over micro-batches, Table 3 caption)        */
   int32_t flags;        /* bit set of kd_flags; other bits must be 0                */
+  float teacher_scale;  /* KD_FLAG_TEACHER_FP8 only: > 0, finite                    */
+  int32_t reserved;     /* must be 0                                                */
 } kd_loss_params;
 
 /* Bytes of device workspace kd_loss_fwd_bwd needs for these parameters.
@@ -132,6 +140,13 @@ kd_status kd_loss_fwd(const kd_loss_params* params,
                       float* loss, float* per_token_loss,
                       void* workspace, size_t workspace_bytes,
                       void* hip_stream);
+
+/* Quantise n values to OCP e4m3 bytes (KD_FLAG_TEACHER_FP8):  dst[i] = e4m3(src[i] * (1 / scale)), the
+ * reciprocal and the product in fp32, round to nearest even, magnitudes beyond 448 saturate, NaN -> 0x7f.
+ * src: device, src_dtype (KD_BF16 or KD_F32), n values; dst: device, n bytes; both 16-byte aligned.
+ * A good scale is max|src| / 448.  The frozen teacher head is quantised once, hidden states per batch. */
+kd_status kd_quantize_e4m3(const void* src, int32_t src_dtype, int64_t n, float scale, void* dst,
+                           void* hip_stream);
 
 /* Multi-teacher distillation (Table 1, "Multi-Teacher Distillation"): n_teachers teachers over the
  * same tokens and vocabulary, each with its own hidden states h_t[k] [T, H_t[k]] and head W_t[k];

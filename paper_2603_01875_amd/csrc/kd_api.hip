@@ -32,7 +32,12 @@ kd_status check_params(const kd_loss_params* p) {
       !(p->beta > 0.f && p->beta < 1.f))
     return KD_ERR_PARAM;
   if (p->accumulate_grad_W != 0 && p->accumulate_grad_W != 1) return KD_ERR_PARAM;
-  if (p->flags & ~(int32_t)KD_FLAG_TAU2) return KD_ERR_PARAM;
+  if (p->flags & ~(int32_t)(KD_FLAG_TAU2 | KD_FLAG_TEACHER_FP8)) return KD_ERR_PARAM;
+  if (p->flags & KD_FLAG_TEACHER_FP8) {
+    if (!(p->teacher_scale > 0.f && p->teacher_scale < INFINITY)) return KD_ERR_PARAM;
+    if (p->in_dtype != KD_BF16) return KD_ERR_UNSUPPORTED;     // the student side stays bf16
+    if (p->H_t % 128) return KD_ERR_ALIGN;                     // fp8 k-steps are 128 elements
+  }
   if (p->w_layout != KD_W_VH) return KD_ERR_UNSUPPORTED;
   return KD_OK;
 }
@@ -50,7 +55,9 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward) {
   // split into bf16 high and low parts laid side by side along K (three products recover all
   // but the low x low term); bf16 inputs with an odd hidden size are zero-padded along K.
   q.in_f32 = p->in_dtype == KD_F32;
-  q.K_t = (int)round_up(q.in_f32 ? 3 * q.H_t : q.H_t, 64);
+  q.t_fp8 = (p->flags & KD_FLAG_TEACHER_FP8) ? 1 : 0;
+  q.t_scale = q.t_fp8 ? p->teacher_scale : 1.f;
+  q.K_t = (int)round_up(q.in_f32 ? 3 * q.H_t : q.H_t, 64);      // fp8: H_t % 128 == 0, used as it is
   q.K_s = (int)round_up(q.in_f32 ? 3 * q.H_s : q.H_s, 64);
   q.prep_Wt = q.in_f32 || q.K_t != q.H_t;
   q.prep_Ws = q.in_f32 || q.K_s != q.H_s;
@@ -114,8 +121,9 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward) {
   }
   // the only buffers whose size depends on the teacher come last, so that everything above sits at
   // the same offsets for every teacher of a multi-teacher call
-  if (q.prep_ht) L.prep_h_t = take((size_t)q.T * q.K_t * 2);
-  if (q.prep_Wt) L.prep_W_t = take((size_t)q.V * q.K_t * 2);
+  const size_t t_es = q.t_fp8 ? 1 : 2;
+  if (q.prep_ht) L.prep_h_t = take((size_t)q.T * q.K_t * t_es);
+  if (q.prep_Wt) L.prep_W_t = take((size_t)q.V * q.K_t * t_es);
   L.total = off;
 }
 
@@ -178,7 +186,9 @@ struct ProfileScope {
 // Re-pack the operands that need it (fp32 split / K padding) into the workspace.
 kd_status prepare_operands(const Problem& q, hipStream_t st) {
   const int* map = q.mask ? q.rowmap : nullptr;     // gather valid tokens to the front
-  if (q.prep_ht)
+  if (q.prep_ht && q.t_fp8)     // rows of H_t bytes are gathered as rows of H_t / 2 two-byte words
+    KD_TRY(kd::launch_prepare(q.user_h_t, 0, q.T, q.H_t / 2, const_cast<void*>(q.h_t), q.K_t / 2, 2, map, q.meta, st));
+  else if (q.prep_ht)
     KD_TRY(kd::launch_prepare(q.user_h_t, q.in_f32, q.T, q.H_t, const_cast<void*>(q.h_t), q.K_t, 2, map, q.meta, st));
   if (q.prep_Wt)
     KD_TRY(kd::launch_prepare(q.user_W_t, q.in_f32, q.V, q.H_t, const_cast<void*>(q.W_t), q.K_t, 1, nullptr, q.meta, st));
@@ -338,6 +348,7 @@ kd_status kd_loss_workspace_size_multi(const kd_loss_params* params, int n_teach
                                        size_t* bytes) {
   if (!bytes || !params || !H_t) return KD_ERR_NULL;
   if (n_teachers < 1 || n_teachers > 16) return KD_ERR_PARAM;
+  if (params->flags & KD_FLAG_TEACHER_FP8) return KD_ERR_UNSUPPORTED;   // one scale cannot serve several teachers
   size_t need = 0;
   for (int k = 0; k < n_teachers; ++k) {
     kd_loss_params pk = *params;
@@ -358,6 +369,7 @@ kd_status kd_loss_fwd_bwd_multi(const kd_loss_params* params, int n_teachers, co
                                 size_t workspace_bytes, void* hip_stream) {
   if (!params || !h_t || !W_t || !H_t || !weights) return KD_ERR_NULL;
   if (n_teachers < 1 || n_teachers > 16) return KD_ERR_PARAM;
+  if (params->flags & KD_FLAG_TEACHER_FP8) return KD_ERR_UNSUPPORTED;
   // all checks for all teachers before the first launch
   Problem q[16];
   Layout L[16];
@@ -383,6 +395,17 @@ kd_status kd_loss_fwd_bwd_multi(const kd_loss_params* params, int n_teachers, co
     s = run_backward(q[k], st, k == 0, k + 1 == n_teachers);
     if (s != KD_OK) return s;
   }
+  return KD_OK;
+}
+
+kd_status kd_quantize_e4m3(const void* src, int32_t src_dtype, int64_t n, float scale, void* dst,
+                           void* hip_stream) {
+  if (!src || !dst) return KD_ERR_NULL;
+  if (n < 1 || n > ((int64_t)1 << 40)) return KD_ERR_SHAPE;
+  if (src_dtype != KD_BF16 && src_dtype != KD_F32) return KD_ERR_PARAM;
+  if (!(scale > 0.f && scale < INFINITY)) return KD_ERR_PARAM;
+  if (!aligned16(src) || !aligned16(dst)) return KD_ERR_ALIGN;
+  KD_TRY(kd::launch_quantize_e4m3(src, src_dtype == KD_F32, n, 1.f / scale, dst, static_cast<hipStream_t>(hip_stream)));
   return KD_OK;
 }
 

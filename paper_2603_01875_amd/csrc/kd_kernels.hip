@@ -70,6 +70,7 @@ struct LogitArgs {
   int bb;              // grad kernel: block width of the work map along the vocabulary (bb | n_vt)
   float c;             // log2(e) / tau
   float beta;
+  float t_scale;       // fp8 teacher: z_t = t_scale * (product of the e4m3 codes); 1 otherwise
   int T_pad;
   float* partials;     // stats: [n_split*4][5][T_pad];  jsd: [n_split*4][2][T_pad]
   const f32x4* rowinfo;// [T_pad]: {lse2_t, lse2_s, mask/(n tau), row term}
@@ -77,16 +78,23 @@ struct LogitArgs {
   int ldz;
 };
 
+// TF8: the teacher operands are e4m3 bytes (one byte per element, 128 elements per k-step)
+template <bool TF8>
 __device__ __forceinline__ WorkItem logit_item(const LogitArgs& a, int vt, int tt) {
   WorkItem it;
   it.A0 = a.W_s + (int64_t)vt * BM * a.H_s;
-  it.A1 = a.W_t + (int64_t)vt * BM * a.H_t;
   it.B0 = a.h_s + (int64_t)tt * BN * a.H_s;
-  it.B1 = a.h_t + (int64_t)tt * BN * a.H_t;
+  if (TF8) {
+    it.A1 = (const bf16_t*)((const char*)a.W_t + (int64_t)vt * BM * a.H_t);
+    it.B1 = (const bf16_t*)((const char*)a.h_t + (int64_t)tt * BN * a.H_t);
+  } else {
+    it.A1 = a.W_t + (int64_t)vt * BM * a.H_t;
+    it.B1 = a.h_t + (int64_t)tt * BN * a.H_t;
+  }
   it.a_rows = min(BM, a.V - vt * BM);
   it.b_rows = min(BN, a.T - tt * BN);
   it.nk0 = a.H_s / BK;
-  it.nk1 = a.H_t / BK;
+  it.nk1 = a.H_t / (TF8 ? 2 * BK : BK);
   it.m0 = vt * BM;
   it.n0 = tt * BN;
   it.aux = 0;
@@ -94,6 +102,7 @@ __device__ __forceinline__ WorkItem logit_item(const LogitArgs& a, int vt, int t
 }
 
 // One workgroup = one (token tile, vocabulary split); it walks the split's tiles in order.
+template <bool TF8>
 struct SplitWork {
   const LogitArgs& a;
   int tt, split, lo, cnt;
@@ -109,10 +118,11 @@ struct SplitWork {
     cnt = hi - lo;
   }
   __device__ int n_items() const { return cnt; }
-  __device__ WorkItem item(int i) const { return logit_item(a, a.vt0 + lo + i, tt); }
+  __device__ WorkItem item(int i) const { return logit_item<TF8>(a, a.vt0 + lo + i, tt); }
 };
 
 // Persistent workgroups striding over the (token tile x vocabulary tile) grid of a chunk.
+template <bool TF8>
 struct ChunkWork {
   const LogitArgs& a;
   int L, G, n_tiles, n_tt, ba;
@@ -127,7 +137,7 @@ struct ChunkWork {
   __device__ WorkItem item(int i) const {
     int tt, vt;
     block_decode(i * G + L, n_tt, ba, a.bb, tt, vt);
-    return logit_item(a, a.vt0 + vt, tt);
+    return logit_item<TF8>(a, a.vt0 + vt, tt);
   }
 };
 
@@ -143,6 +153,17 @@ constexpr float LN2 = 0.6931471805599453f;
 
 __device__ __forceinline__ float fexp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float flog2(float x) { return __builtin_amdgcn_logf(x); }
+
+// fp8 teacher: the accumulator holds the product of the e4m3 codes; bring it to logits.
+__device__ __forceinline__ void scale_teacher(AccTile& accT, float ts) {
+  if (ts == 1.f) return;
+#pragma unroll
+  for (int mt = 0; mt < MI; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < NI; ++nt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) accT[mt][nt][r] *= ts;
+}
 
 // Rows of A beyond the vocabulary (last tile only) must not contribute: give them a
 // huge negative logit in both accumulators (their exp is 0, their difference is 0).
@@ -167,9 +188,9 @@ __device__ __forceinline__ void mask_tail_rows(const WorkItem& it, AccTile& accS
 template <int KIND>
 struct StatsEpi {
   float m_t[NI], S_t[NI], m_s[NI], S_s[NI], X[NI];
-  float c;
+  float c, ts;
   int wm, wn, lane;
-  __device__ StatsEpi(float c_) : c(c_) {
+  __device__ StatsEpi(float c_, float ts_) : c(c_), ts(ts_) {
     lane = threadIdx.x & 63;
     wm = (threadIdx.x >> 6) & 1;
     wn = threadIdx.x >> 7;
@@ -178,6 +199,7 @@ struct StatsEpi {
   }
   __device__ void begin_item(const WorkItem&) {}
   __device__ void end_item(const WorkItem& it, AccTile& accS, AccTile& accT) {
+    scale_teacher(accT, ts);
     mask_tail_rows(it, accS, accT, wm, lane);
 #pragma unroll
     for (int nt = 0; nt < NI; ++nt) {
@@ -273,9 +295,9 @@ struct RowTerm {
 template <int KIND>
 struct RowsEpi {
   float A1[NI], A2[NI], Lt[NI], Ls[NI];
-  float c, w;
+  float c, w, ts;
   int wm, wn, lane;
-  __device__ RowsEpi(const LogitArgs& a, int tt) : c(a.c), w(a.beta) {
+  __device__ RowsEpi(const LogitArgs& a, int tt) : c(a.c), w(a.beta), ts(a.t_scale) {
     lane = threadIdx.x & 63;
     wm = (threadIdx.x >> 6) & 1;
     wn = threadIdx.x >> 7;
@@ -287,6 +309,7 @@ struct RowsEpi {
   }
   __device__ void begin_item(const WorkItem&) {}
   __device__ void end_item(const WorkItem& it, AccTile& accS, AccTile& accT) {
+    scale_teacher(accT, ts);
     mask_tail_rows(it, accS, accT, wm, lane);
 #pragma unroll
     for (int nt = 0; nt < NI; ++nt) {
@@ -336,6 +359,7 @@ struct GradEpi {
     }
   }
   __device__ void end_item(const WorkItem& it, AccTile& accS, AccTile& accT) {
+    scale_teacher(accT, a.t_scale);
     const float c = a.c, w = a.beta;
     const int mloc0 = it.m0 - a.vt0 * BM;      // vocabulary offset inside the chunk
 #pragma unroll
@@ -378,30 +402,30 @@ struct GradEpi {
 #define KD_LOGIT_KERNEL __global__ __launch_bounds__(LCfg::NT)
 #define KD_GEMM_KERNEL __global__ __launch_bounds__(GCfg::NT)
 
-template <int KIND>
+template <int KIND, bool TF8>
 KD_LOGIT_KERNEL void stats_kernel(const LogitArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  SplitWork work(a);
-  StatsEpi<KIND> epi(a.c);
-  tile_loop<2, LCfg>(work, epi, a.H_s, a.H_t, a.H_s, a.H_t, smem);
+  SplitWork<TF8> work(a);
+  StatsEpi<KIND> epi(a.c, a.t_scale);
+  tile_loop<2, LCfg, 0, TF8>(work, epi, a.H_s, a.H_t, a.H_s, a.H_t, smem);
   if (work.cnt > 0) epi.write(a, work.tt, work.split);
 }
 
-template <int KIND>
+template <int KIND, bool TF8>
 KD_LOGIT_KERNEL void rows_kernel(const LogitArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  SplitWork work(a);
+  SplitWork<TF8> work(a);
   RowsEpi<KIND> epi(a, work.tt);
-  tile_loop<2, LCfg>(work, epi, a.H_s, a.H_t, a.H_s, a.H_t, smem);
+  tile_loop<2, LCfg, 0, TF8>(work, epi, a.H_s, a.H_t, a.H_s, a.H_t, smem);
   if (work.cnt > 0) epi.write(a, work.tt, work.split);
 }
 
-template <int KIND>
+template <int KIND, bool TF8>
 KD_LOGIT_KERNEL void grad_kernel(const LogitArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  ChunkWork work(a);
+  ChunkWork<TF8> work(a);
   GradEpi<KIND> epi(a);
-  tile_loop<2, LCfg>(work, epi, a.H_s, a.H_t, a.H_s, a.H_t, smem);
+  tile_loop<2, LCfg, 0, TF8>(work, epi, a.H_s, a.H_t, a.H_s, a.H_t, smem);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -711,6 +735,41 @@ __global__ void prepare_kernel(const void* src, int src_f32, int R, int H, bf16_
   dst[i] = v;
 }
 
+// OCP e4m3 (4 exponent bits, bias 7, 3 mantissa bits, no infinities, 0x7f = NaN, largest 448):
+// round to nearest even, magnitudes beyond 448 saturate to 448.
+__device__ __forceinline__ uint32_t f32_to_e4m3(float x) {
+  const uint32_t u = __float_as_uint(x);
+  const uint32_t sign = (u >> 24) & 0x80u;
+  const float a = fabsf(x);
+  if (!(a == a)) return sign | 0x7fu;
+  if (a >= 448.f) return sign | 0x7eu;
+  if (a < 0.015625f) return sign | (uint32_t)__builtin_rintf(a * 512.f);   // steps of 2^-9; 8 = smallest normal
+  const uint32_t ua = u & 0x7fffffffu;
+  const uint32_t m = ua & 0x7fffffu, rem = m & 0xfffffu;
+  uint32_t code = (((ua >> 23) - 120u) << 3) | (m >> 20);                   // exponent re-biased 127 -> 7
+  if (rem > 0x80000u || (rem == 0x80000u && (code & 1u))) ++code;           // a carry moves into the exponent
+  return sign | code;
+}
+
+// dst[i] = e4m3(src[i] * inv_scale), 8 values per thread
+__global__ void quantize_e4m3_kernel(const void* src, int src_f32, int64_t n, float inv_scale, uint8_t* dst) {
+  const int64_t i0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 8;
+  if (i0 >= n) return;
+  uint32_t w[2] = {0u, 0u};
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const int64_t i = i0 + k;
+    float x = 0.f;
+    if (i < n) x = src_f32 ? ((const float*)src)[i] : (float)((const bf16_t*)src)[i];
+    w[k >> 2] |= f32_to_e4m3(x * inv_scale) << (8 * (k & 3));
+  }
+  if (i0 + 8 <= n) {
+    *(uint2*)(dst + i0) = make_uint2(w[0], w[1]);
+  } else {
+    for (int k = 0; i0 + k < n; ++k) dst[i0 + k] = (uint8_t)(w[k >> 2] >> (8 * (k & 3)));
+  }
+}
+
 // grad_h_s row t = sum over split-K parts of the fp32 partial sums of its compacted row (zero for a
 // masked token), converted to the output dtype.
 __global__ void gradh_finish_kernel(const float* parts, int n_parts, int T, int H, const int* inv,
@@ -762,6 +821,7 @@ static LogitArgs make_logit_args(const Problem& p) {
   a.meta = p.meta;
   a.c = 1.4426950408889634f / p.tau;
   a.beta = p.beta;
+  a.t_scale = p.t_fp8 ? p.t_scale : 1.f;
   a.T_pad = p.T_pad;
   a.rowinfo = (const f32x4*)p.rowinfo;
   return a;
@@ -772,11 +832,14 @@ hipError_t launch_stats(const Problem& p, hipStream_t st) {
   a.vt0 = 0; a.n_vt = p.n_vt;
   a.partials = p.partials;
   const int grid = p.n_tt * p.n_split;      // worst case; workgroups beyond the device-side plan exit
+#define KD_STATS(K) (p.t_fp8 ? launch_big(stats_kernel<K, true>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
+                            : launch_big(stats_kernel<K, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a))
   switch (p.kind) {
-    case 0: return launch_big(stats_kernel<0>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
-    case 1: return launch_big(stats_kernel<1>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
-    default: return launch_big(stats_kernel<2>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);   // log-sum-exps only
+    case 0: return KD_STATS(0);
+    case 1: return KD_STATS(1);
+    default: return KD_STATS(2);   // log-sum-exps only
   }
+#undef KD_STATS
 }
 
 hipError_t launch_rows(const Problem& p, hipStream_t st) {
@@ -784,12 +847,15 @@ hipError_t launch_rows(const Problem& p, hipStream_t st) {
   a.vt0 = 0; a.n_vt = p.n_vt;
   a.partials = p.partials;
   const int grid = p.n_tt * p.n_split;
+#define KD_ROWS(K) (p.t_fp8 ? launch_big(rows_kernel<K, true>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
+                           : launch_big(rows_kernel<K, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a))
   switch (p.kind) {
-    case 2: return launch_big(rows_kernel<2>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
-    case 3: return launch_big(rows_kernel<3>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
-    case 4: return launch_big(rows_kernel<4>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
-    default: return launch_big(rows_kernel<5>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
+    case 2: return KD_ROWS(2);
+    case 3: return KD_ROWS(3);
+    case 4: return KD_ROWS(4);
+    default: return KD_ROWS(5);
   }
+#undef KD_ROWS
 }
 
 hipError_t launch_rowmap(const Problem& p, hipStream_t st) {
@@ -824,14 +890,17 @@ hipError_t launch_grad_chunk(const Problem& p, int v0, int width, hipStream_t st
   a.dz = (bf16_t*)p.dz; a.ldz = p.V_c;
   const int tiles = p.n_tt * a.n_vt;
   int grid = tiles < p.n_cu ? tiles : p.n_cu;
+#define KD_GRAD(K) (p.t_fp8 ? launch_big(grad_kernel<K, true>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
+                           : launch_big(grad_kernel<K, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a))
   switch (p.kind) {
-    case 0: return launch_big(grad_kernel<0>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
-    case 1: return launch_big(grad_kernel<1>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
-    case 2: return launch_big(grad_kernel<2>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
-    case 3: return launch_big(grad_kernel<3>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
-    case 4: return launch_big(grad_kernel<4>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
-    default: return launch_big(grad_kernel<5>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
+    case 0: return KD_GRAD(0);
+    case 1: return KD_GRAD(1);
+    case 2: return KD_GRAD(2);
+    case 3: return KD_GRAD(3);
+    case 4: return KD_GRAD(4);
+    default: return KD_GRAD(5);
   }
+#undef KD_GRAD
 }
 
 hipError_t launch_transpose(const void* src, int64_t ld_src, int R, int C, void* dst, int64_t ld_dst, int R_pad,
@@ -869,6 +938,13 @@ hipError_t launch_prepare(const void* src, int src_f32, int R, int H, void* dst,
   const int64_t n = (int64_t)R * K;
   hipLaunchKernelGGL(prepare_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, src, src_f32, R, H,
                      (bf16_t*)dst, K, split_mode, rowmap, meta);
+  return hipGetLastError();
+}
+
+hipError_t launch_quantize_e4m3(const void* src, int src_f32, int64_t n, float inv_scale, void* dst, hipStream_t st) {
+  const int64_t threads = (n + 7) / 8;
+  hipLaunchKernelGGL(quantize_e4m3_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, src, src_f32, n,
+                     inv_scale, (uint8_t*)dst);
   return hipGetLastError();
 }
 

@@ -26,6 +26,8 @@ struct Problem {
   const void *h_t, *W_t, *h_s, *W_s;                   // bf16 [rows][K_t or K_s] as the kernels read them
   const void *user_h_t, *user_W_t, *user_h_s, *user_W_s;  // the caller's arrays
   int in_f32;                   // inputs are fp32
+  int t_fp8;                    // teacher operands are e4m3 bytes (K_t = H_t elements = bytes per row)
+  float t_scale;                // ... and z_t = t_scale * (product of the codes)
   int prep_ht, prep_Wt, prep_hs, prep_Ws;   // which operands are re-packed into the workspace
   int K_t, K_s;                 // contraction lengths of the (re-packed) logit operands, multiples of 64
   const uint8_t* mask;
@@ -65,6 +67,7 @@ struct GemmDesc {
 };
 
 hipError_t launch_rowmap(const Problem& p, hipStream_t st);
+hipError_t launch_quantize_e4m3(const void* src, int src_f32, int64_t n, float inv_scale, void* dst, hipStream_t st);
 hipError_t launch_stats(const Problem& p, hipStream_t st);
 hipError_t launch_combine(const Problem& p, hipStream_t st);
 hipError_t launch_rows(const Problem& p, hipStream_t st);

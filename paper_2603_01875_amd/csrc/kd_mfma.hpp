@@ -195,7 +195,16 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-template <int NPHASE, class Cfg, int KM = 0, class Work, class Epi>
+//
+// fp8 second phase (P1F8).  The operands of phase 1 may be OCP e4m3 bytes instead of bf16: a
+// k-step then covers 128 elements (the same 128 bytes per tile row, so loads, LDS layout and
+// synchronisation are unchanged) and is multiplied by 2 x MI x NI MFMAs 32x32x64 (f8f6f4,
+// unit scales), each lane holding 32 consecutive bytes of its row per operand.  Both
+// operands use the same byte-to-lane map, so the order of k inside an instruction does not
+// matter.  ld*1 are then in bytes (= elements).
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+
+template <int NPHASE, class Cfg, int KM = 0, bool P1F8 = false, class Work, class Epi>
 __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
                                           const int lda0, const int lda1, const int ldb0, const int ldb1,
                                           char* smem) {
@@ -208,6 +217,8 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
   constexpr int CPR_A = Cfg::BM / 8, CPR_B = BN / 8;                 // chunks per k-row
   constexpr int KPL_A = Cfg::NT / CPR_A, KPL_B = Cfg::NT / CPR_B;    // k-rows per load instruction
   static_assert(KM == 0 || (KPL_A % 4 == 0 && KPL_B % 4 == 0 && BK % 16 == 0), "k-major swizzle");
+  static_assert(!P1F8 || (KM == 0 && NPHASE == 2 && BK == 64 && Cfg::LOADS_BEFORE_BARRIER == LOADS),
+                "fp8 phase: 128-byte rows, every load of a k-step issued before its barrier");
   typedef typename Cfg::Acc Acc;
 
   const int tid = threadIdx.x;
@@ -269,7 +280,8 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
       int r = lrow + Cfg::ROWS_PER_LOAD * (isA ? j : j - A_LOADS);
       const int lim = isA ? li.a_rows : li.b_rows;
       r = r < lim ? r : lim - 1;
-      loff[j] = ((uint32_t)r * (isA ? la : lb) + lchunk * 8) * 2;
+      const uint32_t es = (P1F8 && l_phase) ? 1 : 2;       // bytes per element
+      loff[j] = (uint32_t)r * (isA ? la : lb) * es + lchunk * 16;
     }
     if (KM) km_offsets(0);
     if (AKM) l_step_a = (int64_t)BK * 2 * la;
@@ -329,6 +341,12 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
   for (int ks = 0; ks < KS; ++ks) fk[ks] = ((2 * ks + (lane >> 5)) ^ fsw) << 4;
   const int a_base = (wm * 32 * MI + frow) * ROWB;
   const int b_base = A_STAGE_BYTES + (wn * 32 * NI + frow) * ROWB;
+  // fp8 fragment (sub-step s of 64 bytes, lane half hb): chunks 4 s + 2 hb and the next one
+  int fk8[2][2];
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) fk8[sb][j] = ((4 * sb + 2 * (lane >> 5) + j) ^ fsw) << 4;
 
   // k-major fragments: byte offset of the lane's first transposing read of sub-step 0
   int kma_f[MI], kmb_f[NI];
@@ -368,6 +386,41 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
       else bfr[nt] = *(const bf16x8*)(base + b_base + nt * 32 * ROWB + fk[ks]);
     }
   };
+  auto read_frags8 = [&](int st, auto s_c, i32x8 (&af)[MI], i32x8 (&bfr)[NI]) {
+    constexpr int sb = decltype(s_c)::value;
+    const char* base = smem + st * STAGE_BYTES;
+#pragma unroll
+    for (int mt = 0; mt < MI; ++mt) {
+      const u32x4 lo = *(const u32x4*)(base + a_base + mt * 32 * ROWB + fk8[sb][0]);
+      const u32x4 hi = *(const u32x4*)(base + a_base + mt * 32 * ROWB + fk8[sb][1]);
+      af[mt] = __builtin_bit_cast(i32x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    }
+#pragma unroll
+    for (int nt = 0; nt < NI; ++nt) {
+      const u32x4 lo = *(const u32x4*)(base + b_base + nt * 32 * ROWB + fk8[sb][0]);
+      const u32x4 hi = *(const u32x4*)(base + b_base + nt * 32 * ROWB + fk8[sb][1]);
+      bfr[nt] = __builtin_bit_cast(i32x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    }
+  };
+  auto mma8 = [&](Acc& acc, const i32x8 (&af)[MI], const i32x8 (&bfr)[NI]) {
+#pragma unroll
+    for (int mt = 0; mt < MI; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < NI; ++nt)
+        acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(af[mt], bfr[nt], acc[mt][nt], 0, 0, 0, 0, 0, 0);
+  };
+  // one fp8 sub-step: per MFMA (64 cycles) a share of the fragment reads and of the loads
+  auto schedule_substep8 = [&](auto n_ds_c, auto n_vm_c) {
+    constexpr int n_mfma = MI * NI, n_ds = decltype(n_ds_c)::value, n_vm = decltype(n_vm_c)::value;
+    constexpr int ds_per = (n_ds + n_mfma - 1) / n_mfma, vm_per = (n_vm + n_mfma - 1) / n_mfma;
+#pragma unroll
+    for (int i = 0; i < n_mfma; ++i) {
+      __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
+      if (ds_per > 0) __builtin_amdgcn_sched_group_barrier(SG_DSREAD, ds_per, 0);
+      if (vm_per > 0) __builtin_amdgcn_sched_group_barrier(SG_VMEM, vm_per, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
   // waits for the k-major fragments about to be multiplied (no-op for K-contiguous operands,
   // whose reads the compiler tracks itself)
   auto wait_frags = [&](AFrag (&af)[MI], BFrag (&bfr)[NI]) {
@@ -405,9 +458,31 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
   // Fragments of sub-step 0 of the k-step about to be consumed; kept across k-steps.
   AFrag fa0[MI];
   BFrag fb0[NI];
+  i32x8 ga0[MI], gb0[NI];   // the same for an fp8 k-step
+
+  // One fp8 k-step (two sub-steps of 64 bytes).  On entry ga0/gb0 hold sub-step 0; on exit the
+  // first fragments of the next k-step are on their way, fp8 ones if NEXT8, else bf16 ones.
+  auto kstep8 = [&](Acc& acc, auto next8_c) {
+    constexpr bool NEXT8 = decltype(next8_c)::value != 0;
+    i32x8 ga1[MI], gb1[NI];
+    const int next = stage == NST - 1 ? 0 : stage + 1;
+    read_frags8(stage, IntC<1>{}, ga1, gb1);
+    issue_loads(fill, 0, LOADS);
+    mma8(acc, ga0, gb0);
+    schedule_substep8(IntC<2 * (MI + NI)>{}, IntC<LOADS>{});
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(Cfg::WAIT_STEADY) : "memory");
+    if constexpr (NEXT8) read_frags8(next, IntC<0>{}, ga0, gb0);
+    else read_frags(next, IntC<0>{}, fa0, fb0);
+    mma8(acc, ga1, gb1);
+    schedule_substep8(IntC<(NEXT8 ? 2 : 1) * (MI + NI)>{}, IntC<0>{});
+    advance();
+    fill = stage;
+    stage = next;
+  };
 
   // One k-step.  On entry fa0/fb0 hold sub-step 0.
-  auto kstep = [&](Acc& acc) {
+  auto kstep = [&](Acc& acc, auto next8_c) {
+    constexpr bool NEXT8 = decltype(next8_c)::value != 0;
     AFrag fa1[MI];
     BFrag fb1[NI];
     const int next = stage == NST - 1 ? 0 : stage + 1;
@@ -432,7 +507,8 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
     // last sub-step (KS-1, odd): multiplies (fa1, fb1), fetches sub-step 0 of the next k-step
     wait_frags(fa1, fb1);
     issue_loads(fill, Cfg::LOADS_BEFORE_BARRIER, LOADS);
-    read_frags(next, IntC<0>{}, fa0, fb0);
+    if constexpr (NEXT8) read_frags8(next, IntC<0>{}, ga0, gb0);
+    else read_frags(next, IntC<0>{}, fa0, fb0);
     mma(acc, fa1, fb1);
     schedule_substep();
     advance();
@@ -452,9 +528,16 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
   for (int c_item = 0; c_item < n_items; ++c_item) {
     const WorkItem ci = work.item(c_item);
     epi.begin_item(ci);
-    for (int k = 0; k < ci.nk0; ++k) kstep(acc0);
-    if (NPHASE > 1)
-      for (int k = 0; k < ci.nk1; ++k) kstep(acc1);
+    if constexpr (P1F8) {
+      for (int k = 1; k < ci.nk0; ++k) kstep(acc0, IntC<0>{});
+      kstep(acc0, IntC<1>{});
+      for (int k = 1; k < ci.nk1; ++k) kstep8(acc1, IntC<1>{});
+      kstep8(acc1, IntC<0>{});
+    } else {
+      for (int k = 0; k < ci.nk0; ++k) kstep(acc0, IntC<0>{});
+      if (NPHASE > 1)
+        for (int k = 0; k < ci.nk1; ++k) kstep(acc1, IntC<0>{});
+    }
     epi.end_item(ci, acc0, acc1);
     Cfg::zero(acc0);
     if (NPHASE > 1) Cfg::zero(acc1);

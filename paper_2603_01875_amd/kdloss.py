@@ -26,7 +26,8 @@ class KdLossParams(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int64), ("H_t", ctypes.c_int64), ("H_s", ctypes.c_int64), ("V", ctypes.c_int64),
                 ("in_dtype", ctypes.c_int32), ("grad_dtype", ctypes.c_int32), ("w_layout", ctypes.c_int32),
                 ("kind", ctypes.c_int32), ("tau", ctypes.c_float), ("beta", ctypes.c_float),
-                ("accumulate_grad_W", ctypes.c_int32), ("flags", ctypes.c_int32)]
+                ("accumulate_grad_W", ctypes.c_int32), ("flags", ctypes.c_int32),
+                ("teacher_scale", ctypes.c_float), ("reserved", ctypes.c_int32)]
 
 
 class KdLossError(RuntimeError):
@@ -62,6 +63,8 @@ def lib():
                                             ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_float),
                                             vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.kd_loss_fwd_bwd_multi.restype = ctypes.c_int
+        L.kd_quantize_e4m3.argtypes = [vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, vp, vp]
+        L.kd_quantize_e4m3.restype = ctypes.c_int
         L.kd_loss_profile_hook.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_void_p), ctypes.c_int]
         L.kd_loss_profile_hook.restype = ctypes.c_int
         L.kd_loss_profile_count.argtypes = []
@@ -73,14 +76,27 @@ def lib():
 
 
 FLAG_TAU2 = 1
-
+FLAG_TEACHER_FP8 = 2
 
 def make_params(T, H_t, H_s, V, kind=FKL, tau=1.0, beta=0.5, in_dtype=BF16, grad_dtype=None,
-                w_layout=W_VH, accumulate_grad_W=False, flags=0):
+                w_layout=W_VH, accumulate_grad_W=False, flags=0, teacher_scale=0.0):
     if grad_dtype is None:
         grad_dtype = in_dtype
     return KdLossParams(int(T), int(H_t), int(H_s), int(V), int(in_dtype), int(grad_dtype), int(w_layout),
-                        int(kind), float(tau), float(beta), int(bool(accumulate_grad_W)), int(flags))
+                        int(kind), float(tau), float(beta), int(bool(accumulate_grad_W)), int(flags),
+                        float(teacher_scale), 0)
+
+
+def quantize_e4m3(x, scale, out=None):
+    """e4m3 codes (uint8 tensor of x's shape) of x / scale; x is a contiguous bf16 or fp32 CUDA tensor."""
+    import torch
+    if out is None:
+        out = torch.empty(x.shape, dtype=torch.uint8, device=x.device)
+    st = lib().kd_quantize_e4m3(_ptr(x), BF16 if x.dtype == torch.bfloat16 else F32, x.numel(), float(scale),
+                                _ptr(out), ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    if st != KD_OK:
+        raise KdLossError(st)
+    return out
 
 
 def kd_loss_workspace_size(params: KdLossParams) -> int:
@@ -167,19 +183,21 @@ def alloc_workspace(params, device="cuda"):
 
 def kd_loss_fwd_bwd(h_t, W_t, h_s, W_s, mask=None, tau=1.0, kind=FKL, beta=0.5, w_layout=W_VH,
                     grad_dtype=None, workspace=None, grad_W_s=None, accumulate_grad_W=False,
-                    want_per_token=True, flags=0):
+                    want_per_token=True, flags=0, teacher_scale=0.0):
     """Convenience wrapper: allocates outputs (and the workspace unless given) and calls the library.
 
     h_t [T,H_t], h_s [T,H_s]; W_t, W_s in `w_layout` ([V,H] for W_VH).  Returns a dict of CUDA tensors.
+    With FLAG_TEACHER_FP8, h_t and W_t are uint8 tensors of e4m3 codes and teacher_scale their joint scale.
     """
     import torch
-    in_dtype = BF16 if h_t.dtype == torch.bfloat16 else F32
+    in_dtype = BF16 if h_s.dtype == torch.bfloat16 else F32
     T, H_t = h_t.shape
     H_s = h_s.shape[1]
     V = W_t.shape[0] if w_layout == W_VH else W_t.shape[1]
     if grad_dtype is None:
         grad_dtype = in_dtype
-    p = make_params(T, H_t, H_s, V, kind, tau, beta, in_dtype, grad_dtype, w_layout, accumulate_grad_W, flags)
+    p = make_params(T, H_t, H_s, V, kind, tau, beta, in_dtype, grad_dtype, w_layout, accumulate_grad_W, flags,
+                    teacher_scale)
     tdt = torch.bfloat16 if grad_dtype == BF16 else torch.float32
     dev = h_t.device
     if workspace is None:
@@ -228,13 +246,14 @@ def kd_loss_fwd_bwd_multi(h_ts, W_ts, weights, h_s, W_s, mask=None, tau=1.0, kin
     return dict(loss=loss, per_token_loss=ptl, grad_h_s=grad_h, grad_W_s=grad_W)
 
 
-def kd_loss_fwd(h_t, W_t, h_s, W_s, mask=None, tau=1.0, kind=FKL, beta=0.5, w_layout=W_VH, workspace=None):
+def kd_loss_fwd(h_t, W_t, h_s, W_s, mask=None, tau=1.0, kind=FKL, beta=0.5, w_layout=W_VH, workspace=None,
+                flags=0, teacher_scale=0.0):
     import torch
-    in_dtype = BF16 if h_t.dtype == torch.bfloat16 else F32
+    in_dtype = BF16 if h_s.dtype == torch.bfloat16 else F32
     T, H_t = h_t.shape
     H_s = h_s.shape[1]
     V = W_t.shape[0] if w_layout == W_VH else W_t.shape[1]
-    p = make_params(T, H_t, H_s, V, kind, tau, beta, in_dtype, in_dtype, w_layout)
+    p = make_params(T, H_t, H_s, V, kind, tau, beta, in_dtype, in_dtype, w_layout, False, flags, teacher_scale)
     dev = h_t.device
     if workspace is None:
         workspace = alloc_workspace(p, dev)

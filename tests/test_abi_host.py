@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layout_matches_header():
-    assert ctypes.sizeof(K.KdLossParams) == 4 * 8 + 8 * 4
+    assert ctypes.sizeof(K.KdLossParams) == 4 * 8 + 10 * 4          # 72 bytes, no padding
 
 
 def test_status_strings():
@@ -61,6 +61,11 @@ def test_workspace_is_far_below_T_times_V():
     (dict(kind=K.JSD, beta=0.0), 4), (dict(kind=K.JSD, beta=1.0), 4), (dict(kind=K.SKEW_FKL, beta=0.0), 4),
     (dict(kind=K.SKEW_RKL, beta=1.5), 4), (dict(kind=-1), 4), (dict(in_dtype=5), 4),
     (dict(w_layout=K.W_HV), 6),
+    # fp8 teacher: needs a positive finite scale, a bf16 student side and H_t % 128 == 0
+    (dict(flags=K.FLAG_TEACHER_FP8), 4), (dict(flags=K.FLAG_TEACHER_FP8, teacher_scale=float("inf")), 4),
+    (dict(flags=K.FLAG_TEACHER_FP8, teacher_scale=1.0, in_dtype=K.F32), 6),
+    (dict(flags=K.FLAG_TEACHER_FP8, teacher_scale=1.0, H_t=4160), 3),
+    (dict(flags=8), 4),
 ])
 def test_bad_params_are_rejected(kw, status):
     with pytest.raises(K.KdLossError) as e:
@@ -99,3 +104,25 @@ def test_pointer_checks_run_before_any_gpu_work():
     assert call(a) == 3
     assert call(good, n - 1) == 5
     assert L.kd_loss_fwd_bwd(None, *good, ctypes.c_size_t(n), None) == 1
+
+
+def test_fp8_teacher_params_and_workspace():
+    bf = K.kd_loss_workspace_size(_ws())
+    f8 = K.kd_loss_workspace_size(_ws(flags=K.FLAG_TEACHER_FP8, teacher_scale=1e-4))
+    assert f8 < bf                                  # the compacted teacher hidden states are half the size
+    # one scale cannot describe several teachers
+    p = _ws(flags=K.FLAG_TEACHER_FP8, teacher_scale=1e-4)
+    H = (ctypes.c_int64 * 2)(4096, 4096)
+    n = ctypes.c_size_t(0)
+    assert K.lib().kd_loss_workspace_size_multi(ctypes.byref(p), 2, H, ctypes.byref(n)) == 6
+
+
+def test_quantize_argument_checks():
+    L = K.lib()
+    a, b = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x2000)
+    assert L.kd_quantize_e4m3(None, K.BF16, 16, 1.0, b, None) == 1
+    assert L.kd_quantize_e4m3(a, K.BF16, 0, 1.0, b, None) == 2
+    assert L.kd_quantize_e4m3(a, 7, 16, 1.0, b, None) == 4
+    assert L.kd_quantize_e4m3(a, K.BF16, 16, 0.0, b, None) == 4
+    assert L.kd_quantize_e4m3(a, K.BF16, 16, float("nan"), b, None) == 4
+    assert L.kd_quantize_e4m3(ctypes.c_void_p(0x1004), K.BF16, 16, 1.0, b, None) == 3

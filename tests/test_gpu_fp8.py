@@ -1,0 +1,125 @@
+"""GPU tests of the fp8 teacher head (KD_FLAG_TEACHER_FP8): the teacher hidden states and head are
+e4m3 codes with one scale each, the teacher logit tiles run on the fp8 matrix pipe.  Parity is against
+the fp64 oracle fed with the DE-QUANTISED teacher arrays, i.e. the exact values the codes stand for,
+so the tolerances are the ones of the bf16 path.  The quantiser kernel is checked bit for bit."""
+import numpy as np
+import pytest
+
+from paper_2603_01875_amd import inputs as I
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _chunk_env(monkeypatch):
+    monkeypatch.delenv("KD_VOCAB_CHUNK", raising=False)
+
+
+def _run_fp8(cfg, data, f8, forward_only=False):
+    import torch
+    from paper_2603_01875_amd import kdloss as K
+    q_h = torch.from_numpy(f8["q_h_t"]).cuda()
+    q_W = torch.from_numpy(f8["q_W_t"]).cuda()
+    h_s = G.to_device(data["h_s"], cfg.dtype)
+    W_s = G.to_device(data["W_s"], cfg.dtype)
+    mask = None if data["mask"] is None else torch.from_numpy(data["mask"]).cuda()
+    kw = dict(tau=cfg.tau, kind=cfg.kind, beta=cfg.beta, flags=K.FLAG_TEACHER_FP8, teacher_scale=f8["teacher_scale"])
+    out = (K.kd_loss_fwd if forward_only else K.kd_loss_fwd_bwd)(q_h, q_W, h_s, W_s, mask, **kw)
+    torch.cuda.synchronize()
+    return out
+
+
+def _oracle_fp8(cfg, data, f8):
+    d = dict(data)
+    d["h_t"], d["W_t"] = f8["h_t"], f8["W_t"]
+    return G.run_oracle(cfg, d)
+
+
+@pytest.mark.parametrize("src", ["bf16", "f32"])
+def test_quantiser_is_bit_exact(src):
+    import torch
+    from paper_2603_01875_amd import kdloss as K
+    rng = np.random.default_rng(11)
+    n = 100003                                            # ragged: not a multiple of 8
+    x = (rng.standard_normal(n) * np.exp(rng.uniform(-9, 7, n))).astype(np.float32)
+    x[:12] = [0.0, -0.0, 1.0625, 1.1875, 2.0 ** -10, 3 * 2.0 ** -10, 447.9, 448.0, 464.0, -1e9, np.inf, np.nan]
+    if src == "bf16":
+        x = I.round_to_bf16(x)
+    xd = torch.from_numpy(x).cuda()
+    if src == "bf16":
+        xd = xd.to(torch.bfloat16)
+    for scale in (1.0, 0.37, 3.0e-3):
+        got = K.quantize_e4m3(xd, scale).cpu().numpy()
+        want = I.quantize_e4m3(x, scale)
+        np.testing.assert_array_equal(got, want)
+
+
+KINDS = [("fkl_bf16", I.FKL, 0.5), ("rkl_bf16", I.RKL, 0.5), ("jsd_bf16", I.JSD, 0.5), ("long_peaked", I.JSD, 0.1)]
+
+
+@pytest.mark.parametrize("name,kind,beta", KINDS)
+def test_fp8_teacher_ragged_multi_tile(name, kind, beta, monkeypatch):
+    # 3 token tiles (last one ragged), 20 vocabulary tiles (last one 8 rows), 5 chunks, 3 fp8 k-steps
+    monkeypatch.setenv("KD_VOCAB_CHUNK", "512")
+    cfg = I.scaled(I.workload(name), batch=3, seq=200, H_t=384, H_s=128, V=2440)
+    data = I.generate(cfg)
+    f8 = I.fp8_teacher(data)
+    out = _run_fp8(cfg, data, f8)
+    G.check(out, _oracle_fp8(cfg, data, f8), name + " fp8 teacher")
+    keep = data["mask"].astype(bool)
+    assert (G.to_host(out["grad_h_s"])[~keep] == 0).all()
+
+
+@pytest.mark.parametrize("kind,beta", [(I.TVD, 0.5), (I.SKEW_FKL, 0.1), (I.SKEW_RKL, 0.1)])
+def test_fp8_teacher_other_divergences(kind, beta):
+    cfg = I.scaled(I.workload("fkl_bf16"), batch=2, seq=150, H_t=128, H_s=64, V=1000, kind=kind, beta=beta)
+    data = I.generate(cfg)
+    f8 = I.fp8_teacher(data)
+    d = dict(data); d["h_t"], d["W_t"] = f8["h_t"], f8["W_t"]
+    extra = G.tvd_tie_allowance(cfg, d) if kind == I.TVD else None
+    G.check(_run_fp8(cfg, data, f8), _oracle_fp8(cfg, data, f8), f"kind {kind} fp8 teacher", extra)
+
+
+@pytest.mark.parametrize("H_t", [128, 256, 1024])
+def test_fp8_teacher_hidden_sizes_and_temperature(H_t):
+    cfg = I.scaled(I.workload("fkl_bf16"), batch=1, seq=300, H_t=H_t, H_s=64, V=776, tau=2.5, mask="ones")
+    data = I.generate(cfg)
+    f8 = I.fp8_teacher(data)
+    G.check(_run_fp8(cfg, data, f8), _oracle_fp8(cfg, data, f8), f"H_t={H_t} fp8 teacher")
+
+
+def test_fp8_teacher_forward_only_matches_full_call():
+    cfg = I.scaled(I.workload("jsd_bf16"), batch=2, seq=160, H_t=256, H_s=128, V=1288)
+    data = I.generate(cfg)
+    f8 = I.fp8_teacher(data)
+    full = _run_fp8(cfg, data, f8)
+    fwd = _run_fp8(cfg, data, f8, forward_only=True)
+    assert float(full["loss"].item()) == float(fwd["loss"].item())
+    assert (G.to_host(full["per_token_loss"]) == G.to_host(fwd["per_token_loss"])).all()
+
+
+def test_codes_that_bf16_holds_exactly_give_the_bf16_result():
+    """e4m3 values are exactly representable in bf16: feeding the de-quantised teacher to the bf16
+    path must give the same loss to fp32 accumulation accuracy (same products, other summation order)."""
+    import torch
+    cfg = I.scaled(I.workload("fkl_bf16"), batch=2, seq=140, H_t=256, H_s=64, V=1000)
+    data = I.generate(cfg)
+    f8 = I.fp8_teacher(data)
+    a = _run_fp8(cfg, data, f8)
+    # power-of-two scales keep the de-quantised values bf16-exact: re-quantise with such scales
+    d = dict(data)
+    tab = I.e4m3_values()
+    q = {}
+    for k in ("h_t", "W_t"):
+        s = float(2.0 ** np.ceil(np.log2(np.abs(data[k]).max() / 448.0)))
+        q[k] = (I.quantize_e4m3(data[k], s), s)
+        d[k] = (tab[q[k][0]] * s).astype(np.float32)
+        assert (I.round_to_bf16(d[k]) == d[k]).all()
+    f8p = dict(q_h_t=q["h_t"][0], q_W_t=q["W_t"][0], teacher_scale=q["h_t"][1] * q["W_t"][1])
+    a = _run_fp8(cfg, data, f8p)
+    b = G.run_gpu(cfg, d)
+    la, lb = float(a["loss"].item()), float(b["loss"].item())
+    assert abs(la - lb) <= 1e-5 * abs(lb)
+    ga, gb = G.to_host(a["grad_W_s"]), G.to_host(b["grad_W_s"])
+    assert np.abs(ga - gb).max() <= 2e-2 * np.abs(gb).max()
