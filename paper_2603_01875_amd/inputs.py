@@ -99,16 +99,22 @@ def quantize_e4m3(x: np.ndarray, scale: float) -> np.ndarray:
     """uint8 e4m3 codes of x * (1 / scale), the reciprocal and the product in fp32: nearest
     representable value, ties to the even code, magnitudes beyond 448 saturate, NaN -> 0x7f | sign.
     Written as a search over the value table, not as bit manipulation."""
-    y = (np.asarray(x, dtype=np.float32) * (np.float32(1.0) / np.float32(scale))).astype(np.float32)
+    x = np.asarray(x, dtype=np.float32)
+    inv = np.float32(1.0) / np.float32(scale)
     pos = e4m3_values()[:127]                       # codes 0x00..0x7e: 0 .. 448, increasing
-    a = np.abs(y).astype(np.float64)
-    hi = np.clip(np.searchsorted(pos, a, side="left"), 1, 126)
-    lo = hi - 1
-    d_lo, d_hi = a - pos[lo], pos[hi] - a
-    code = np.where(d_lo < d_hi, lo, np.where(d_hi < d_lo, hi, np.where(lo % 2 == 0, lo, hi)))
-    code = np.where(a >= 448.0, 126, code)
-    code = np.where(np.isnan(a), 127, code)
-    return (code | np.where(np.signbit(y), 128, 0)).astype(np.uint8)
+    out = np.empty(x.shape, dtype=np.uint8)
+    xf, of = x.reshape(-1), out.reshape(-1)
+    for i0 in range(0, xf.size, 1 << 24):           # blocks only bound the temporaries
+        y = (xf[i0:i0 + (1 << 24)] * inv).astype(np.float32)
+        a = np.abs(y).astype(np.float64)
+        hi = np.clip(np.searchsorted(pos, a, side="left"), 1, 126)
+        lo = hi - 1
+        d_lo, d_hi = a - pos[lo], pos[hi] - a
+        code = np.where(d_lo < d_hi, lo, np.where(d_hi < d_lo, hi, np.where(lo % 2 == 0, lo, hi)))
+        code = np.where(a >= 448.0, 126, code)
+        code = np.where(np.isnan(a), 127, code)
+        of[i0:i0 + (1 << 24)] = (code | np.where(np.signbit(y), 128, 0)).astype(np.uint8)
+    return out
 
 
 def fp8_teacher(data: dict) -> dict:
