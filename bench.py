@@ -127,6 +127,9 @@ def main():
             torch.cuda.synchronize()
         fam[name] = sum(t.durations_ms())
 
+    # the matrix pipe's own ceiling on this machine, measured right after the timed region (a few ms)
+    probe = K.probe_mfma_rate()
+
     n_valid = int(data["mask"].sum())
     # masked tokens are compacted away on the device: the kernels work on the valid tokens, rounded up
     # to whole 256-token tiles; flop figures count exactly those rows
@@ -157,7 +160,9 @@ def main():
                    "valid_tokens": n_valid, "computed_token_rows": T_comp, "w_layout": "VH", "teacher_fp8": bool(args.teacher_fp8), "vocab_chunk": vc, "launches_per_step": n_launch},
         "roofline": {"bound": "mfma", "kernel": "stats_kernel", "achieved": stats_tflops,
                      "peak": peak, "unit": "TFLOP/s", "frac": stats_tflops / peak,
-                     "traffic": traffic, "launch_ms": stats_avg, "flop_per_launch": logit_flop},
+                     "traffic": traffic, "launch_ms": stats_avg, "flop_per_launch": logit_flop,
+                     "mfma_only_probe_tflops": probe,
+                     "frac_of_probe": None if args.teacher_fp8 else stats_tflops / probe},
         "tflops_algorithmic": flop_alg / (ms_per_step * 1e-3) / 1e12,
         "tflops_executed": flop_exec / (ms_per_step * 1e-3) / 1e12,
         "mfma_frac_whole_step": (flop_exec / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS if not args.teacher_fp8 else

@@ -191,6 +191,15 @@ kd_status kd_loss_profile_hook(int which, void** events, int n_events);
 /* Pairs recorded since the hook was set. */
 int kd_loss_profile_count(void);
 
+/* Benchmark aid, not part of the method: what the bf16 matrix pipe sustains on this GPU with nothing
+ * else going on.  One launch of 256 workgroups x 8 waves (the occupancy of the logit kernels), each wave
+ * issuing `iters` x 8 independent MFMA 32x32x16 on operands taken from `operands` (device, 128 KiB of
+ * bf16 values; the shader clock under this load depends on them, so pass values like real data).
+ * Executes KD_PROBE_FLOP_PER_ITER * iters flop.  `sink` (device, 256 * 512 floats) receives sums that
+ * only keep the work alive.  Time the launch with events on `hip_stream`. */
+#define KD_PROBE_FLOP_PER_ITER (256.0 * 8 * 8 * 2 * 32 * 32 * 16)
+kd_status kd_probe_mfma_rate(const void* operands, int iters, float* sink, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -409,6 +409,14 @@ kd_status kd_quantize_e4m3(const void* src, int32_t src_dtype, int64_t n, float 
   return KD_OK;
 }
 
+kd_status kd_probe_mfma_rate(const void* operands, int iters, float* sink, void* hip_stream) {
+  if (!operands || !sink) return KD_ERR_NULL;
+  if (iters < 1 || iters > (1 << 24)) return KD_ERR_PARAM;
+  if (!aligned16(operands) || !aligned16(sink)) return KD_ERR_ALIGN;
+  KD_TRY(kd::launch_mfma_probe(operands, iters, sink, kd::kNumCU, static_cast<hipStream_t>(hip_stream)));
+  return KD_OK;
+}
+
 kd_status kd_loss_profile_hook(int which, void** events, int n_events) {
   if (which < 0) {
     g_hook = ProfileHook{};

@@ -735,6 +735,37 @@ __global__ void prepare_kernel(const void* src, int src_f32, int R, int H, bf16_
   dst[i] = v;
 }
 
+// Measurement aid: what the matrix pipe sustains with nothing else going on.  Same occupancy as the
+// logit kernels (one workgroup of 8 waves per CU, forced by the LDS request), 8 independent 32x32x16
+// accumulators per wave, operands taken from the caller's buffer (the shader clock under MFMA load
+// depends on the operand values, so they should look like real data).
+__global__ __launch_bounds__(512) void mfma_probe_kernel(const bf16x8* operands, int iters, float* sink) {
+  const int lane_id = (blockIdx.x * 512 + threadIdx.x) & 2047;      // 2048 x 4 x 16 B = 128 KiB of operands
+  bf16x8 a0 = operands[lane_id * 4 + 0], a1 = operands[lane_id * 4 + 1];
+  bf16x8 b0 = operands[lane_id * 4 + 2], b1 = operands[lane_id * 4 + 3];
+  f32x16 c[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) c[i][r] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+    c[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, c[0], 0, 0, 0);
+    c[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, c[1], 0, 0, 0);
+    c[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, c[2], 0, 0, 0);
+    c[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, c[3], 0, 0, 0);
+    c[4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b0, a0, c[4], 0, 0, 0);
+    c[5] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b1, a0, c[5], 0, 0, 0);
+    c[6] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b0, a1, c[6], 0, 0, 0);
+    c[7] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b1, a1, c[7], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += c[i][r];
+  sink[blockIdx.x * 512 + threadIdx.x] = s;
+}
+
 // OCP e4m3 (4 exponent bits, bias 7, 3 mantissa bits, no infinities, 0x7f = NaN, largest 448):
 // round to nearest even, magnitudes beyond 448 saturate to 448.
 __device__ __forceinline__ uint32_t f32_to_e4m3(float x) {
@@ -939,6 +970,15 @@ hipError_t launch_prepare(const void* src, int src_f32, int R, int H, void* dst,
   hipLaunchKernelGGL(prepare_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, src, src_f32, R, H,
                      (bf16_t*)dst, K, split_mode, rowmap, meta);
   return hipGetLastError();
+}
+
+hipError_t launch_mfma_probe(const void* operands, int iters, float* sink, int n_cu, hipStream_t st) {
+  struct { const bf16x8* o; int it; float* s; } a{(const bf16x8*)operands, iters, sink};
+  hipError_t e = hipFuncSetAttribute((const void*)mfma_probe_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     LCfg::SMEM_BYTES);
+  if (e != hipSuccess) return e;
+  void* params[] = {&a.o, &a.it, &a.s};
+  return hipLaunchKernel((const void*)mfma_probe_kernel, dim3(n_cu), dim3(512), params, LCfg::SMEM_BYTES, st);
 }
 
 hipError_t launch_quantize_e4m3(const void* src, int src_f32, int64_t n, float inv_scale, void* dst, hipStream_t st) {

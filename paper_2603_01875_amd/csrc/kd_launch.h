@@ -67,6 +67,7 @@ struct GemmDesc {
 };
 
 hipError_t launch_rowmap(const Problem& p, hipStream_t st);
+hipError_t launch_mfma_probe(const void* operands, int iters, float* sink, int n_cu, hipStream_t st);
 hipError_t launch_quantize_e4m3(const void* src, int src_f32, int64_t n, float inv_scale, void* dst, hipStream_t st);
 hipError_t launch_stats(const Problem& p, hipStream_t st);
 hipError_t launch_combine(const Problem& p, hipStream_t st);

@@ -65,6 +65,8 @@ def lib():
         L.kd_loss_fwd_bwd_multi.restype = ctypes.c_int
         L.kd_quantize_e4m3.argtypes = [vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, vp, vp]
         L.kd_quantize_e4m3.restype = ctypes.c_int
+        L.kd_probe_mfma_rate.argtypes = [vp, ctypes.c_int, vp, vp]
+        L.kd_probe_mfma_rate.restype = ctypes.c_int
         L.kd_loss_profile_hook.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_void_p), ctypes.c_int]
         L.kd_loss_profile_hook.restype = ctypes.c_int
         L.kd_loss_profile_count.argtypes = []
@@ -146,6 +148,29 @@ class KernelTimer:
 
     def durations_ms(self):
         return [self.events[2 * i].elapsed_time(self.events[2 * i + 1]) for i in range(self.count)]
+
+
+PROBE_FLOP_PER_ITER = 256.0 * 8 * 8 * 2 * 32 * 32 * 16
+
+
+def probe_mfma_rate(iters=20000, repeats=3):
+    """TFLOP/s of an MFMA-only loop on random bf16 operands (best of `repeats`): the matrix-pipe
+    ceiling of this GPU at the clock it holds under that load."""
+    import torch
+    ops = torch.randn(64 * 1024, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    sink = torch.empty(256 * 512, device="cuda", dtype=torch.float32)
+    s = torch.cuda.current_stream().cuda_stream
+    best = 0.0
+    for _ in range(repeats + 1):                 # first launch warms up
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        st = lib().kd_probe_mfma_rate(_ptr(ops), int(iters), _ptr(sink), ctypes.c_void_p(s))
+        if st != KD_OK:
+            raise KdLossError(st)
+        e1.record()
+        torch.cuda.synchronize()
+        best = max(best, PROBE_FLOP_PER_ITER * iters / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+    return best
 
 
 def _ptr(t):
