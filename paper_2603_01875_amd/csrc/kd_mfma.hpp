@@ -1,16 +1,17 @@
-// Device-side building blocks for the bf16 MFMA kernels of libkdloss (gfx950).
+// Device-side building blocks for the MFMA kernels of libkdloss (gfx950).
 //
 // Every contraction on the hot path (teacher logits, student logits, and the
-// two backward products; paper Sec. 3.1-3.2) is brought to one form:
-//     D[m][n] = sum_k A[m][k] * B[n][k]
-// with both operands stored K-contiguous ("row m of A" and "row n of B" are
-// contiguous runs of K bf16 values).  One workgroup of 256 threads (4 waves,
-// 2 x 2) owns a 128 (M) x 256 (N) tile; each wave owns 64 x 128 of it as
-// 2 x 4 MFMA 32x32x16 blocks.  The M axis is the register axis of the MFMA
-// result (a lane holds 4 consecutive m for one n), the N axis the lane axis.
-// For the logit tiles M = vocabulary and N = tokens, so the per-token
-// reductions over the vocabulary are in-lane and need no cross-lane traffic
-// inside the vocabulary loop.
+// two backward products; paper Sec. 3.1-3.2) has the form
+//     D[m][n] = sum_k A[m][k] * B[n][k].
+// An operand is normally stored K-contiguous ("row m of A" is a contiguous run
+// of K bf16 values); the backward products also take one operand stored the
+// other way round (k-major, see tile_loop).  One workgroup owns a BM (M) x 256
+// (N) tile, its waves arranged 2 (M) x WN (N), each wave owning MI x NI MFMA
+// 32x32x16 blocks.  The M axis is the register axis of the MFMA result (a lane
+// holds 4 consecutive m for one n), the N axis the lane axis.  For the logit
+// tiles M = vocabulary and N = tokens, so the per-token reductions over the
+// vocabulary are in-lane and need no cross-lane traffic inside the vocabulary
+// loop.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
