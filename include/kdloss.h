@@ -153,9 +153,11 @@ kd_status kd_quantize_e4m3(const void* src, int32_t src_dtype, int64_t n, float 
  *   loss = sum_k weights[k] * D(p_t^k, p_s)      (same divergence, temperature and mask for all)
  * and the gradients are those of that sum.  params->H_t is ignored; h_t, W_t, H_t, weights are HOST
  * arrays of n_teachers entries (the pointers in h_t / W_t are device pointers).  1 <= n_teachers <= 16.
- * Everything else is as for kd_loss_fwd_bwd; the workspace must satisfy the _multi size query.  The
- * student logits are recomputed once per teacher; grad_h_s is accumulated over teachers in fp32,
- * grad_W_s in the output dtype. */
+ * Everything else is as for kd_loss_fwd_bwd; the workspace must satisfy the _multi size query (the
+ * single-teacher workspace plus, per teacher, its row statistics and any re-packed operand copies).
+ * The token compaction, the student operands and the two backward products are shared: each chunk of
+ * dL/dz_s is summed over the teachers (in its bf16 staging buffer) before grad_W_s and grad_h_s are
+ * formed once.  The student logit tiles are recomputed with every teacher's tiles. */
 kd_status kd_loss_workspace_size_multi(const kd_loss_params* params, int n_teachers, const int64_t* H_t,
                                        size_t* bytes);
 kd_status kd_loss_fwd_bwd_multi(const kd_loss_params* params, int n_teachers,

@@ -14,8 +14,11 @@ inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 struct Layout {
-  size_t meta, rowmap, inv, rowinfo, row_loss, partials, h_sT, dz, gh32, total;
-  size_t prep_h_t, prep_W_t, prep_h_s, prep_W_s;   // re-packed operands (only when needed)
+  size_t meta, rowmap, inv, row_loss, partials, h_sT, dz, gh32;
+  size_t prep_h_s, prep_W_s;                       // re-packed student operands (only when needed)
+  size_t common;                                   // end of everything above: the same for every teacher
+  size_t rowinfo, prep_h_t, prep_W_t;              // per-teacher block (row statistics, re-packed operands)
+  size_t total;                                    // end of this teacher's block
 };
 
 kd_status check_params(const kd_loss_params* p) {
@@ -42,8 +45,9 @@ kd_status check_params(const kd_loss_params* p) {
   return KD_OK;
 }
 
-// Tile counts, vocabulary chunk and split factors.  Depends on the params only.
-void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward) {
+// Tile counts, vocabulary chunk and split factors.  Depends on the params only.  The per-teacher
+// block is placed at `teacher_base` (default: right after the common part).
+void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward, size_t teacher_base = 0) {
   q.T = (int)p->T; q.V = (int)p->V; q.H_s = (int)p->H_s; q.H_t = (int)p->H_t;
   q.kind = p->kind; q.tau = p->tau; q.beta = p->beta;
   q.grad_f32 = p->grad_dtype == KD_F32;
@@ -106,7 +110,6 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward) {
   L.meta = take(64);
   L.rowmap = take((size_t)q.T_pad * 4);
   L.inv = take((size_t)q.T * 4);
-  L.rowinfo = take((size_t)q.T_pad * 16);
   L.row_loss = take((size_t)q.T_pad * 4);
   L.partials = take((size_t)q.n_split * 4 * 5 * q.T_pad * 4);
   L.prep_h_t = L.prep_W_t = L.prep_h_s = L.prep_W_s = 0;
@@ -119,8 +122,11 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward) {
   } else {
     L.h_sT = L.dz = L.gh32 = off;
   }
-  // the only buffers whose size depends on the teacher come last, so that everything above sits at
-  // the same offsets for every teacher of a multi-teacher call
+  // what belongs to one teacher comes last, so that everything above sits at the same offsets for
+  // every teacher of a multi-teacher call and the teachers' blocks can lie side by side
+  L.common = off;
+  if (teacher_base > off) off = teacher_base;
+  L.rowinfo = take((size_t)q.T_pad * 16);
   const size_t t_es = q.t_fp8 ? 1 : 2;
   if (q.prep_ht) L.prep_h_t = take((size_t)q.T * q.K_t * t_es);
   if (q.prep_Wt) L.prep_W_t = take((size_t)q.V * q.K_t * t_es);
@@ -183,26 +189,28 @@ struct ProfileScope {
     if ((expr) != hipSuccess) return KD_ERR_LAUNCH; \
   } while (0)
 
-// Re-pack the operands that need it (fp32 split / K padding) into the workspace.
-kd_status prepare_operands(const Problem& q, hipStream_t st) {
+// Re-pack the operands that need it (fp32 split / K padding / compaction) into the workspace.
+kd_status prepare_operands(const Problem& q, hipStream_t st, bool student, bool teacher) {
   const int* map = q.mask ? q.rowmap : nullptr;     // gather valid tokens to the front
-  if (q.prep_ht && q.t_fp8)     // rows of H_t bytes are gathered as rows of H_t / 2 two-byte words
+  if (teacher && q.prep_ht && q.t_fp8)     // rows of H_t bytes are gathered as rows of H_t / 2 two-byte words
     KD_TRY(kd::launch_prepare(q.user_h_t, 0, q.T, q.H_t / 2, const_cast<void*>(q.h_t), q.K_t / 2, 2, map, q.meta, st));
-  else if (q.prep_ht)
+  else if (teacher && q.prep_ht)
     KD_TRY(kd::launch_prepare(q.user_h_t, q.in_f32, q.T, q.H_t, const_cast<void*>(q.h_t), q.K_t, 2, map, q.meta, st));
-  if (q.prep_Wt)
+  if (teacher && q.prep_Wt)
     KD_TRY(kd::launch_prepare(q.user_W_t, q.in_f32, q.V, q.H_t, const_cast<void*>(q.W_t), q.K_t, 1, nullptr, q.meta, st));
-  if (q.prep_hs)
+  if (student && q.prep_hs)
     KD_TRY(kd::launch_prepare(q.user_h_s, q.in_f32, q.T, q.H_s, const_cast<void*>(q.h_s), q.K_s, 2, map, q.meta, st));
-  if (q.prep_Ws)
+  if (student && q.prep_Ws)
     KD_TRY(kd::launch_prepare(q.user_W_s, q.in_f32, q.V, q.H_s, const_cast<void*>(q.W_s), q.K_s, 1, nullptr, q.meta, st));
   return KD_OK;
 }
 
-kd_status run_forward(const Problem& q, hipStream_t st) {
-  KD_TRY(kd::launch_rowmap(q, st));
+// Forward pass of one teacher.  The token compaction and the student operands are shared by the
+// teachers of a call: only the first one makes them.
+kd_status run_forward(const Problem& q, hipStream_t st, bool first_teacher = true) {
+  if (first_teacher) KD_TRY(kd::launch_rowmap(q, st));
   {
-    kd_status ps = prepare_operands(q, st);
+    kd_status ps = prepare_operands(q, st, first_teacher, true);
     if (ps != KD_OK) return ps;
   }
   {
@@ -221,19 +229,22 @@ kd_status run_forward(const Problem& q, hipStream_t st) {
   return KD_OK;
 }
 
-// Backward pass of one teacher: dL/dz_s chunk by chunk and the two products.  grad_h_s is summed in
-// fp32 over the chunks (and over teachers) and converted once, after the last teacher.
-kd_status run_backward(const Problem& q, hipStream_t st, bool first_teacher, bool last_teacher) {
+// Backward pass: dL/dz_s chunk by chunk and the two products.  With several teachers the chunk of
+// dL/dz_s is the sum over the teachers (each gradient kernel adds its weighted share to the bf16
+// staging buffer), so the products run once per chunk whatever the number of teachers.  grad_h_s is
+// summed in fp32 over the chunks and converted once at the end.
+kd_status run_backward(const Problem* qs, int n_teachers, hipStream_t st) {
+  const Problem& q = qs[0];          // everything on the student side is the same for all teachers
   // h_s^T [H_s][T_pad] once (token axis zero-padded): the K-contiguous operand of grad_W_s
   KD_TRY(kd::launch_transpose(q.h_s, q.K_s, q.T, q.H_s, q.h_sT, q.T_pad, q.T_pad, st));
 
   const size_t gsz = q.grad_f32 ? 4 : 2;
-  bool first = first_teacher;      // the fp32 partial sums of grad_h_s run on across teachers
+  bool first = true;
   for (int64_t v0 = 0; v0 < q.V; v0 += q.V_c) {
     const int width = (int)((q.V - v0 < q.V_c) ? q.V - v0 : q.V_c);
-    {
+    for (int k = 0; k < n_teachers; ++k) {
       ProfileScope ps(KD_PROF_GRAD, st);
-      KD_TRY(kd::launch_grad_chunk(q, (int)v0, width, st));
+      KD_TRY(kd::launch_grad_chunk(qs[k], (int)v0, width, k > 0, st));
     }
     kd::GemmDesc gw{};   // grad_W_s[v][h] = sum_t h_sT[h][t] dz[t][v]   (dz read token-major as it lies)
     gw.A = q.h_sT; gw.lda = q.T_pad; gw.M = q.H_s;
@@ -263,7 +274,7 @@ kd_status run_backward(const Problem& q, hipStream_t st, bool first_teacher, boo
     }
     first = false;
   }
-  if (last_teacher) KD_TRY(kd::launch_gradh_finish(q, st));
+  KD_TRY(kd::launch_gradh_finish(q, st));
   return KD_OK;
 }
 
@@ -271,7 +282,7 @@ kd_status run_backward(const Problem& q, hipStream_t st, bool first_teacher, boo
 kd_status check_buffers(const kd_loss_params* params, const void* h_t, const void* W_t, const void* h_s,
                         const void* W_s, const uint8_t* mask, float* loss, void* workspace,
                         size_t workspace_bytes, bool backward, void* grad_h_s, void* grad_W_s,
-                        Problem& q, Layout& L) {
+                        Problem& q, Layout& L, size_t teacher_base = 0) {
   kd_status s = check_params(params);
   if (s != KD_OK) return s;
   if (!h_t || !W_t || !h_s || !W_s || !loss || !workspace) return KD_ERR_NULL;
@@ -279,7 +290,7 @@ kd_status check_buffers(const kd_loss_params* params, const void* h_t, const voi
   if (!aligned16(h_t) || !aligned16(W_t) || !aligned16(h_s) || !aligned16(W_s)) return KD_ERR_ALIGN;
   if (backward && (!aligned16(grad_h_s) || !aligned16(grad_W_s))) return KD_ERR_ALIGN;
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return KD_ERR_ALIGN;
-  plan(params, q, L, backward);
+  plan(params, q, L, backward, teacher_base);
   if (workspace_bytes < L.total) return KD_ERR_WORKSPACE;
   q.h_t = h_t; q.W_t = W_t; q.h_s = h_s; q.W_s = W_s; q.mask = mask;
   q.loss = loss;
@@ -341,7 +352,7 @@ kd_status kd_loss_fwd_bwd(const kd_loss_params* params, const void* h_t, const v
 
   s = run_forward(q, st);
   if (s != KD_OK) return s;
-  return run_backward(q, st, true, true);
+  return run_backward(&q, 1, st);
 }
 
 kd_status kd_loss_workspace_size_multi(const kd_loss_params* params, int n_teachers, const int64_t* H_t,
@@ -349,16 +360,18 @@ kd_status kd_loss_workspace_size_multi(const kd_loss_params* params, int n_teach
   if (!bytes || !params || !H_t) return KD_ERR_NULL;
   if (n_teachers < 1 || n_teachers > 16) return KD_ERR_PARAM;
   if (params->flags & KD_FLAG_TEACHER_FP8) return KD_ERR_UNSUPPORTED;   // one scale cannot serve several teachers
-  size_t need = 0;
+  size_t base = 0;                       // teacher blocks lie side by side after the common part
   for (int k = 0; k < n_teachers; ++k) {
     kd_loss_params pk = *params;
     pk.H_t = H_t[k];
-    size_t b = 0;
-    kd_status s = kd_loss_workspace_size(&pk, &b);
+    kd_status s = check_params(&pk);
     if (s != KD_OK) return s;
-    if (b > need) need = b;
+    Problem q{};
+    Layout L{};
+    plan(&pk, q, L, true, base);
+    base = L.total;
   }
-  *bytes = need;
+  *bytes = base;
   return KD_OK;
 }
 
@@ -373,29 +386,26 @@ kd_status kd_loss_fwd_bwd_multi(const kd_loss_params* params, int n_teachers, co
   // all checks for all teachers before the first launch
   Problem q[16];
   Layout L[16];
+  size_t base = 0;
   for (int k = 0; k < n_teachers; ++k) {
     if (!std::isfinite(weights[k])) return KD_ERR_PARAM;
     kd_loss_params pk = *params;
     pk.H_t = H_t[k];
     q[k] = Problem{};
     kd_status s = check_buffers(&pk, h_t[k], W_t[k], h_s, W_s, mask, loss, workspace, workspace_bytes, true,
-                                grad_h_s, grad_W_s, q[k], L[k]);
+                                grad_h_s, grad_W_s, q[k], L[k], base);
     if (s != KD_OK) return s;
+    base = L[k].total;
     q[k].per_token_loss = per_token_loss;
-    q[k].out_weight *= weights[k];
+    q[k].out_weight *= weights[k];     // scales this teacher's loss and its share of dL/dz_s
     q[k].accumulate_loss = k > 0;
-    if (k > 0) q[k].accumulate_grad_W = 1;
   }
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   for (int k = 0; k < n_teachers; ++k) {
-    // the fp32 partial sums of grad_h_s carry over from teacher to teacher: their offset in the
-    // workspace does not depend on H_t (the teacher operand copies are carved last)
-    kd_status s = run_forward(q[k], st);
-    if (s != KD_OK) return s;
-    s = run_backward(q[k], st, k == 0, k + 1 == n_teachers);
+    kd_status s = run_forward(q[k], st, k == 0);
     if (s != KD_OK) return s;
   }
-  return KD_OK;
+  return run_backward(q, n_teachers, st);
 }
 
 kd_status kd_quantize_e4m3(const void* src, int32_t src_dtype, int64_t n, float scale, void* dst,

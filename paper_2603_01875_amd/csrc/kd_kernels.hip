@@ -76,6 +76,7 @@ struct LogitArgs {
   const f32x4* rowinfo;// [T_pad]: {lse2_t, lse2_s, mask/(n tau), row term}
   bf16_t* dz;          // [T_pad][ldz]   chunk of dL/dz_s, vocabulary contiguous
   int ldz;
+  int dz_accumulate;   // add to dz instead of overwriting it (further teachers of a multi-teacher call)
 };
 
 // TF8: the teacher operands are e4m3 bytes (one byte per element, 128 elements per k-step)
@@ -372,7 +373,9 @@ struct GradEpi {
         for (int q = 0; q < 4; ++q) {
           const int m = acc_m(wm, mt, 4 * q, lane);
           const bool ok = m < it.a_rows;
+          bf16x4* const dst = (bf16x4*)(a.dz + (int64_t)n * a.ldz + mloc0 + m);
           bf16x4 o;
+          if (a.dz_accumulate) o = *dst;
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const float lt = fmaf(accT[mt][nt][4 * q + i], c, -Lt[nt]);
@@ -388,9 +391,9 @@ struct GradEpi {
               g = ps * (RowTerm<KIND>::template eval<false>(lt, ls, w, u1, u2) - R[nt]);
             }
             const float d = ok ? s * g : 0.f;
-            o[i] = (bf16_t)d;
+            o[i] = (bf16_t)(a.dz_accumulate ? (float)o[i] + d : d);
           }
-          *(bf16x4*)(a.dz + (int64_t)n * a.ldz + mloc0 + m) = o;
+          *dst = o;
         }
     }
   }
@@ -913,8 +916,9 @@ hipError_t launch_finalize(const Problem& p, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t launch_grad_chunk(const Problem& p, int v0, int width, hipStream_t st) {
+hipError_t launch_grad_chunk(const Problem& p, int v0, int width, bool accumulate, hipStream_t st) {
   LogitArgs a = make_logit_args(p);
+  a.dz_accumulate = accumulate ? 1 : 0;
   a.vt0 = v0 / BM;
   a.n_vt = (width + BM - 1) / BM;
   a.bb = largest_divisor_le(a.n_vt, 8);

@@ -74,7 +74,7 @@ hipError_t launch_combine(const Problem& p, hipStream_t st);
 hipError_t launch_rows(const Problem& p, hipStream_t st);
 hipError_t launch_combine_rows(const Problem& p, hipStream_t st);
 hipError_t launch_finalize(const Problem& p, hipStream_t st);
-hipError_t launch_grad_chunk(const Problem& p, int v0, int width, hipStream_t st);
+hipError_t launch_grad_chunk(const Problem& p, int v0, int width, bool accumulate, hipStream_t st);
 hipError_t launch_transpose(const void* src, int64_t ld_src, int R, int C, void* dst, int64_t ld_dst, int R_pad,
                             hipStream_t st);
 hipError_t launch_gemm(const GemmDesc& d, int n_cu, hipStream_t st);

@@ -187,6 +187,34 @@ def test_multi_teacher_and_tau2():
     G.check(b, ref, "tau^2")
 
 
+def test_three_teachers_share_the_backward_products(monkeypatch):
+    """Three teachers, several vocabulary chunks, no mask, fp32 gradients: every chunk of dL/dz_s is the
+    weighted sum over the teachers before the two products run once."""
+    import torch
+    from oracle import kd_oracle as O
+    from paper_2603_01875_amd import kdloss as K
+    monkeypatch.setenv("KD_VOCAB_CHUNK", "512")
+    base = I.scaled(I.workload("fkl_bf16"), batch=1, seq=280, H_s=64, V=1800, mask="ones")
+    ds = [I.generate(I.scaled(base, H_t=h, seed=500 + i)) for i, h in enumerate((128, 64, 256))]
+    weights = (0.5, 0.2, 0.3)
+    h_s, W_s = ds[0]["h_s"], ds[0]["W_s"]
+    ref = O.kd_loss_multi([d["h_t"] for d in ds], [d["W_t"] for d in ds], weights, h_s, W_s, None, base.tau,
+                          I.RKL, 0.5, O.W_VH)
+    dev = lambda x: G.to_device(x, I.BF16)
+    out = K.kd_loss_fwd_bwd_multi([dev(d["h_t"]) for d in ds], [dev(d["W_t"]) for d in ds], weights,
+                                  dev(h_s), dev(W_s), None, tau=base.tau, kind=I.RKL, grad_dtype=K.F32)
+    torch.cuda.synchronize()
+    G.check(out, ref, "three teachers")
+    # one teacher through the multi entry point is the single-teacher call
+    one = K.kd_loss_fwd_bwd_multi([dev(ds[0]["h_t"])], [dev(ds[0]["W_t"])], (1.0,), dev(h_s), dev(W_s), None,
+                                  tau=base.tau, kind=I.RKL, grad_dtype=K.F32)
+    single = K.kd_loss_fwd_bwd(dev(ds[0]["h_t"]), dev(ds[0]["W_t"]), dev(h_s), dev(W_s), None, tau=base.tau,
+                               kind=I.RKL, grad_dtype=K.F32)
+    torch.cuda.synchronize()
+    assert float(one["loss"].item()) == float(single["loss"].item())
+    assert torch.equal(one["grad_W_s"], single["grad_W_s"]) and torch.equal(one["grad_h_s"], single["grad_h_s"])
+
+
 @pytest.mark.parametrize("tau", [1.5, 4.0])
 @pytest.mark.parametrize("kind,beta", [(I.FKL, 0.5), (I.RKL, 0.5), (I.JSD, 0.4), (I.TVD, 0.5)])
 def test_ragged_last_tile_with_high_temperature(kind, beta, tau):
