@@ -50,6 +50,8 @@ def main():
     ap.add_argument("--teacher-fp8", action="store_true",
                     help="optional mode, not the headline: teacher hidden states and head quantised to e4m3 "
                          "(one scale each) and the teacher logit tiles on the fp8 matrix pipe")
+    ap.add_argument("--w-layout", choices=("vh", "hv"), default="vh",
+                    help="storage order of the heads: vh = [V,H] (lm_head.weight order, the headline), hv = [H,V]")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (scale for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -70,6 +72,10 @@ def main():
     mask = torch.from_numpy(data["mask"]).cuda()
     T, V, H_t, H_s = cfg.T, cfg.V, cfg.H_t, cfg.H_s
 
+    hv = args.w_layout == "hv"
+    if hv:
+        dev["W_t"] = dev["W_t"].t().contiguous()
+        dev["W_s"] = dev["W_s"].t().contiguous()
     flags, t_scale = 0, 0.0
     if args.teacher_fp8:
         # quantise once (the head is frozen; hidden states would be quantised per batch by one more small kernel)
@@ -78,13 +84,14 @@ def main():
         dev["h_t"] = K.quantize_e4m3(dev["h_t"], s_h)
         dev["W_t"] = K.quantize_e4m3(dev["W_t"], s_W)
         flags, t_scale = K.FLAG_TEACHER_FP8, float(np.float32(s_h) * np.float32(s_W))
-    p = K.make_params(T, H_t, H_s, V, cfg.kind, cfg.tau, cfg.beta, K.BF16, K.BF16, K.W_VH, False, flags, t_scale)
+    p = K.make_params(T, H_t, H_s, V, cfg.kind, cfg.tau, cfg.beta, K.BF16, K.BF16, K.W_HV if hv else K.W_VH, False,
+                      flags, t_scale)
     ws = K.alloc_workspace(p)
     vc, n_launch = K.kd_loss_plan_info(p)
     loss = torch.empty(1, dtype=torch.float32, device="cuda")
     ptl = torch.empty(T, dtype=torch.float32, device="cuda")
     gh = torch.empty((T, H_s), dtype=torch.bfloat16, device="cuda")
-    gW = torch.empty((V, H_s), dtype=torch.bfloat16, device="cuda")
+    gW = torch.empty((H_s, V) if hv else (V, H_s), dtype=torch.bfloat16, device="cuda")
 
     def step():
         K.kd_loss_fwd_bwd_raw(p, dev["h_t"], dev["W_t"], dev["h_s"], dev["W_s"], mask, loss, ptl, gh, gW, ws)
@@ -157,7 +164,7 @@ def main():
         "dtype": "bf16 (teacher operands e4m3)" if args.teacher_fp8 else "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "T": T, "H_t": H_t, "H_s": H_s, "V": V,
                    "kind": {0: "fkl", 1: "rkl", 2: "jsd", 3: "tvd", 4: "skew_fkl", 5: "skew_rkl"}[cfg.kind], "tau": cfg.tau, "beta": cfg.beta,
-                   "valid_tokens": n_valid, "computed_token_rows": T_comp, "w_layout": "VH", "teacher_fp8": bool(args.teacher_fp8), "vocab_chunk": vc, "launches_per_step": n_launch},
+                   "valid_tokens": n_valid, "computed_token_rows": T_comp, "w_layout": args.w_layout.upper(), "teacher_fp8": bool(args.teacher_fp8), "vocab_chunk": vc, "launches_per_step": n_launch},
         "roofline": {"bound": "mfma", "kernel": "stats_kernel", "achieved": stats_tflops,
                      "peak": peak, "unit": "TFLOP/s", "frac": stats_tflops / peak,
                      "traffic": traffic, "launch_ms": stats_avg, "flop_per_launch": logit_flop,

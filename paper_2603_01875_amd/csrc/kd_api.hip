@@ -41,7 +41,12 @@ kd_status check_params(const kd_loss_params* p) {
     if (p->in_dtype != KD_BF16) return KD_ERR_UNSUPPORTED;     // the student side stays bf16
     if (p->H_t % 128) return KD_ERR_ALIGN;                     // fp8 k-steps are 128 elements
   }
-  if (p->w_layout != KD_W_VH) return KD_ERR_UNSUPPORTED;
+  if (p->w_layout == KD_W_HV) {
+    // [H][V] heads are read in place as k-major operands: bf16, whole k-steps, and a vocabulary that
+    // the K-contiguous operand of the grad_h_s product can walk in whole 64-element steps
+    if (p->in_dtype != KD_BF16 || (p->flags & KD_FLAG_TEACHER_FP8)) return KD_ERR_UNSUPPORTED;
+    if (p->H_t % 64 || p->H_s % 64 || p->V % 64) return KD_ERR_UNSUPPORTED;
+  }
   return KD_OK;
 }
 
@@ -59,6 +64,7 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward, si
   // split into bf16 high and low parts laid side by side along K (three products recover all
   // but the low x low term); bf16 inputs with an odd hidden size are zero-padded along K.
   q.in_f32 = p->in_dtype == KD_F32;
+  q.w_hv = p->w_layout == KD_W_HV;
   q.t_fp8 = (p->flags & KD_FLAG_TEACHER_FP8) ? 1 : 0;
   q.t_scale = q.t_fp8 ? p->teacher_scale : 1.f;
   q.K_t = (int)round_up(q.in_f32 ? 3 * q.H_t : q.H_t, 64);      // fp8: H_t % 128 == 0, used as it is
@@ -246,28 +252,41 @@ kd_status run_backward(const Problem* qs, int n_teachers, hipStream_t st) {
       ProfileScope ps(KD_PROF_GRAD, st);
       KD_TRY(kd::launch_grad_chunk(qs[k], (int)v0, width, k > 0, st));
     }
-    kd::GemmDesc gw{};   // grad_W_s[v][h] = sum_t h_sT[h][t] dz[t][v]   (dz read token-major as it lies)
-    gw.A = q.h_sT; gw.lda = q.T_pad; gw.M = q.H_s;
-    gw.B = q.dz; gw.ldb = q.V_c; gw.N = width;
-    gw.k_major = 2; gw.k_rows = q.T_pad;
+    kd::GemmDesc gw{}, gh{};
     gw.K = q.T_pad; gw.k_per_split = 0;
     gw.meta = q.meta; gw.k_from_meta = 1;        // only the token tiles that hold valid tokens
-    gw.out = static_cast<char*>(q.grad_W_s) + (size_t)v0 * q.H_s * gsz;
-    gw.ldo = q.H_s; gw.out_split_stride = 0;
+    gw.out_split_stride = 0;
     gw.out_f32 = q.grad_f32; gw.accumulate = q.accumulate_grad_W;
-    {
-      ProfileScope ps(KD_PROF_GEMM_GRAD_W, st);
-      KD_TRY(kd::launch_gemm(gw, q.n_cu, st));
-    }
-    kd::GemmDesc gh{};   // grad_h_s[t][h] += sum_v W_s[v][h] dz[t][v]   (the head read vocabulary-major as it lies;
-                         // dz is zero from the chunk's last valid column to the end of its 128-column tile)
-    gh.A = static_cast<const char*>(q.W_s) + (size_t)v0 * q.K_s * 2; gh.lda = q.K_s; gh.M = q.H_s;
-    gh.k_major = 1; gh.k_rows = width;
     gh.B = q.dz; gh.ldb = q.V_c; gh.N = q.T;
     gh.meta = q.meta; gh.n_from_meta = 1;        // rows = valid tokens
     gh.K = (int)round_up(width, 64); gh.k_per_split = q.ksteps_h * 64;
     gh.out = q.gh32; gh.ldo = q.H_s; gh.out_split_stride = (int64_t)q.T * q.H_s;
     gh.out_f32 = 1; gh.accumulate = first ? 0 : 1;
+    if (!q.w_hv) {
+      // grad_W_s[v][h] = sum_t h_sT[h][t] dz[t][v]   (dz read token-major as it lies)
+      gw.A = q.h_sT; gw.lda = q.T_pad; gw.M = q.H_s;
+      gw.B = q.dz; gw.ldb = q.V_c; gw.N = width;
+      gw.k_major = 2; gw.k_rows = q.T_pad;
+      gw.out = static_cast<char*>(q.grad_W_s) + (size_t)v0 * q.H_s * gsz; gw.ldo = q.H_s;
+      // grad_h_s[t][h] += sum_v W_s[v][h] dz[t][v]   (the head read vocabulary-major as it lies; dz is
+      // zero from the chunk's last valid column to the end of its 128-column tile)
+      gh.A = static_cast<const char*>(q.W_s) + (size_t)v0 * q.K_s * 2; gh.lda = q.K_s; gh.M = q.H_s;
+      gh.k_major = 1; gh.k_rows = width;
+    } else {
+      // heads stored [H][V]: grad_W_s[h][v] = sum_t dz[t][v] h_sT[h][t], dz again read as it lies, now as
+      // the first operand so that the output rows run along the vocabulary
+      gw.A = q.dz; gw.lda = q.V_c; gw.M = width;
+      gw.B = q.h_sT; gw.ldb = q.T_pad; gw.N = q.H_s;
+      gw.k_major = 1; gw.k_rows = q.T_pad;
+      gw.out = static_cast<char*>(q.grad_W_s) + (size_t)v0 * gsz; gw.ldo = q.V;
+      // grad_h_s[t][h] += sum_v W_s[h][v] dz[t][v]: both operands K-contiguous (V % 64 == 0)
+      gh.A = static_cast<const char*>(q.W_s) + (size_t)v0 * 2; gh.lda = q.V; gh.M = q.H_s;
+      gh.k_major = 0; gh.k_rows = width;
+    }
+    {
+      ProfileScope ps(KD_PROF_GEMM_GRAD_W, st);
+      KD_TRY(kd::launch_gemm(gw, q.n_cu, st));
+    }
     {
       ProfileScope ps(KD_PROF_GEMM_GRAD_H, st);
       KD_TRY(kd::launch_gemm(gh, q.n_cu, st));

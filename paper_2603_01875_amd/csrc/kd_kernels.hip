@@ -65,6 +65,7 @@ __device__ __forceinline__ void block_decode(int q, int na, int ba, int bb, int&
 struct LogitArgs {
   const bf16_t* W_s; const bf16_t* h_s; const bf16_t* W_t; const bf16_t* h_t;
   int T, V, H_s, H_t;  // H_*: contraction length and row stride of the (re-packed) operands
+                       // (heads in [H][V] order: their row stride is V)
   const int* meta;     // device-side plan: valid tokens, token tiles, vocabulary splits, block shape
   int vt0, n_vt;       // vocabulary tiles [vt0, vt0 + n_vt) of BM rows handled by this launch
   int bb;              // grad kernel: block width of the work map along the vocabulary (bb | n_vt)
@@ -79,19 +80,26 @@ struct LogitArgs {
   int dz_accumulate;   // add to dz instead of overwriting it (further teachers of a multi-teacher call)
 };
 
-// TF8: the teacher operands are e4m3 bytes (one byte per element, 128 elements per k-step)
-template <bool TF8>
+// TF8: the teacher operands are e4m3 bytes (one byte per element, 128 elements per k-step).
+// WHV: the heads are stored [H][V] (vocabulary contiguous), i.e. k-major for the logit products.
+template <bool TF8, bool WHV>
 __device__ __forceinline__ WorkItem logit_item(const LogitArgs& a, int vt, int tt) {
   WorkItem it;
-  it.A0 = a.W_s + (int64_t)vt * BM * a.H_s;
   it.B0 = a.h_s + (int64_t)tt * BN * a.H_s;
-  if (TF8) {
+  if (WHV) {
+    it.A0 = a.W_s + vt * BM;
+    it.A1 = a.W_t + vt * BM;
+    it.B1 = a.h_t + (int64_t)tt * BN * a.H_t;
+  } else if (TF8) {
+    it.A0 = a.W_s + (int64_t)vt * BM * a.H_s;
     it.A1 = (const bf16_t*)((const char*)a.W_t + (int64_t)vt * BM * a.H_t);
     it.B1 = (const bf16_t*)((const char*)a.h_t + (int64_t)tt * BN * a.H_t);
   } else {
+    it.A0 = a.W_s + (int64_t)vt * BM * a.H_s;
     it.A1 = a.W_t + (int64_t)vt * BM * a.H_t;
     it.B1 = a.h_t + (int64_t)tt * BN * a.H_t;
   }
+  it.ka_rows = it.kb_rows = 1 << 30;       // hidden sizes are whole k-steps: no k-row is ever missing
   it.a_rows = min(BM, a.V - vt * BM);
   it.b_rows = min(BN, a.T - tt * BN);
   it.nk0 = a.H_s / BK;
@@ -103,7 +111,7 @@ __device__ __forceinline__ WorkItem logit_item(const LogitArgs& a, int vt, int t
 }
 
 // One workgroup = one (token tile, vocabulary split); it walks the split's tiles in order.
-template <bool TF8>
+template <bool TF8, bool WHV>
 struct SplitWork {
   const LogitArgs& a;
   int tt, split, lo, cnt;
@@ -119,11 +127,11 @@ struct SplitWork {
     cnt = hi - lo;
   }
   __device__ int n_items() const { return cnt; }
-  __device__ WorkItem item(int i) const { return logit_item<TF8>(a, a.vt0 + lo + i, tt); }
+  __device__ WorkItem item(int i) const { return logit_item<TF8, WHV>(a, a.vt0 + lo + i, tt); }
 };
 
 // Persistent workgroups striding over the (token tile x vocabulary tile) grid of a chunk.
-template <bool TF8>
+template <bool TF8, bool WHV>
 struct ChunkWork {
   const LogitArgs& a;
   int L, G, n_tiles, n_tt, ba;
@@ -138,7 +146,7 @@ struct ChunkWork {
   __device__ WorkItem item(int i) const {
     int tt, vt;
     block_decode(i * G + L, n_tt, ba, a.bb, tt, vt);
-    return logit_item<TF8>(a, a.vt0 + vt, tt);
+    return logit_item<TF8, WHV>(a, a.vt0 + vt, tt);
   }
 };
 
@@ -405,30 +413,30 @@ struct GradEpi {
 #define KD_LOGIT_KERNEL __global__ __launch_bounds__(LCfg::NT)
 #define KD_GEMM_KERNEL __global__ __launch_bounds__(GCfg::NT)
 
-template <int KIND, bool TF8>
+template <int KIND, bool TF8, bool WHV>
 KD_LOGIT_KERNEL void stats_kernel(const LogitArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  SplitWork<TF8> work(a);
+  SplitWork<TF8, WHV> work(a);
   StatsEpi<KIND> epi(a.c, a.t_scale);
-  tile_loop<2, LCfg, 0, TF8>(work, epi, a.H_s, a.H_t, a.H_s, a.H_t, smem);
+  tile_loop<2, LCfg, WHV ? 1 : 0, TF8>(work, epi, WHV ? a.V : a.H_s, WHV ? a.V : a.H_t, a.H_s, a.H_t, smem);
   if (work.cnt > 0) epi.write(a, work.tt, work.split);
 }
 
-template <int KIND, bool TF8>
+template <int KIND, bool TF8, bool WHV>
 KD_LOGIT_KERNEL void rows_kernel(const LogitArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  SplitWork<TF8> work(a);
+  SplitWork<TF8, WHV> work(a);
   RowsEpi<KIND> epi(a, work.tt);
-  tile_loop<2, LCfg, 0, TF8>(work, epi, a.H_s, a.H_t, a.H_s, a.H_t, smem);
+  tile_loop<2, LCfg, WHV ? 1 : 0, TF8>(work, epi, WHV ? a.V : a.H_s, WHV ? a.V : a.H_t, a.H_s, a.H_t, smem);
   if (work.cnt > 0) epi.write(a, work.tt, work.split);
 }
 
-template <int KIND, bool TF8>
+template <int KIND, bool TF8, bool WHV>
 KD_LOGIT_KERNEL void grad_kernel(const LogitArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  ChunkWork<TF8> work(a);
+  ChunkWork<TF8, WHV> work(a);
   GradEpi<KIND> epi(a);
-  tile_loop<2, LCfg, 0, TF8>(work, epi, a.H_s, a.H_t, a.H_s, a.H_t, smem);
+  tile_loop<2, LCfg, WHV ? 1 : 0, TF8>(work, epi, WHV ? a.V : a.H_s, WHV ? a.V : a.H_t, a.H_s, a.H_t, smem);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -452,7 +460,7 @@ struct GemmArgs {
   int k_rows;          // k-major operand: k-rows that exist in memory (rows beyond are clamped)
 };
 
-// KM: which operand is stored k-major (1: A[k][m], 2: B[k][n]); the other one is K-contiguous.
+// KM: which operand is stored k-major (0: none, 1: A[k][m], 2: B[k][n]); the others are K-contiguous.
 template <int KM>
 struct GemmWork {
   const GemmArgs& a;
@@ -866,8 +874,9 @@ hipError_t launch_stats(const Problem& p, hipStream_t st) {
   a.vt0 = 0; a.n_vt = p.n_vt;
   a.partials = p.partials;
   const int grid = p.n_tt * p.n_split;      // worst case; workgroups beyond the device-side plan exit
-#define KD_STATS(K) (p.t_fp8 ? launch_big(stats_kernel<K, true>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
-                            : launch_big(stats_kernel<K, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a))
+#define KD_STATS(K) (p.t_fp8 ? launch_big(stats_kernel<K, true, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
+                     : p.w_hv ? launch_big(stats_kernel<K, false, true>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
+                              : launch_big(stats_kernel<K, false, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a))
   switch (p.kind) {
     case 0: return KD_STATS(0);
     case 1: return KD_STATS(1);
@@ -881,8 +890,9 @@ hipError_t launch_rows(const Problem& p, hipStream_t st) {
   a.vt0 = 0; a.n_vt = p.n_vt;
   a.partials = p.partials;
   const int grid = p.n_tt * p.n_split;
-#define KD_ROWS(K) (p.t_fp8 ? launch_big(rows_kernel<K, true>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
-                           : launch_big(rows_kernel<K, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a))
+#define KD_ROWS(K) (p.t_fp8 ? launch_big(rows_kernel<K, true, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
+                    : p.w_hv ? launch_big(rows_kernel<K, false, true>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
+                             : launch_big(rows_kernel<K, false, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a))
   switch (p.kind) {
     case 2: return KD_ROWS(2);
     case 3: return KD_ROWS(3);
@@ -925,8 +935,9 @@ hipError_t launch_grad_chunk(const Problem& p, int v0, int width, bool accumulat
   a.dz = (bf16_t*)p.dz; a.ldz = p.V_c;
   const int tiles = p.n_tt * a.n_vt;
   int grid = tiles < p.n_cu ? tiles : p.n_cu;
-#define KD_GRAD(K) (p.t_fp8 ? launch_big(grad_kernel<K, true>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
-                           : launch_big(grad_kernel<K, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a))
+#define KD_GRAD(K) (p.t_fp8 ? launch_big(grad_kernel<K, true, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
+                    : p.w_hv ? launch_big(grad_kernel<K, false, true>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
+                             : launch_big(grad_kernel<K, false, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a))
   switch (p.kind) {
     case 0: return KD_GRAD(0);
     case 1: return KD_GRAD(1);
@@ -963,6 +974,7 @@ hipError_t launch_gemm(const GemmDesc& d, int n_cu, hipStream_t st) {
   a.k_rows = d.k_rows;
   const int tiles = a.n_mt * a.n_nt * a.n_ksplit;       // worst case (no token masked)
   const int grid = tiles < n_cu ? tiles : n_cu;
+  if (d.k_major == 0) return launch_big(gemm_kernel<0>, grid, GCfg::NT, GCfg::SMEM_BYTES, st, &a);
   if (d.k_major == 1) return launch_big(gemm_kernel<1>, grid, GCfg::NT, GCfg::SMEM_BYTES, st, &a);
   if (d.k_major == 2) return launch_big(gemm_kernel<2>, grid, GCfg::NT, GCfg::SMEM_BYTES, st, &a);
   return hipErrorInvalidValue;

@@ -26,6 +26,7 @@ struct Problem {
   const void *h_t, *W_t, *h_s, *W_s;                   // bf16 [rows][K_t or K_s] as the kernels read them
   const void *user_h_t, *user_W_t, *user_h_s, *user_W_s;  // the caller's arrays
   int in_f32;                   // inputs are fp32
+  int w_hv;                     // heads (and grad_W_s) are stored [H][V]
   int t_fp8;                    // teacher operands are e4m3 bytes (K_t = H_t elements = bytes per row)
   float t_scale;                // ... and z_t = t_scale * (product of the codes)
   int prep_ht, prep_Wt, prep_hs, prep_Ws;   // which operands are re-packed into the workspace
@@ -61,7 +62,8 @@ struct GemmDesc {
   const int* meta;        // device-side plan, needed when a flag below is set
   int n_from_meta;        // N = number of valid tokens
   int k_from_meta;        // K = valid tokens rounded up to whole token tiles (no split-K)
-  int k_major;            // 1: A is stored [K][M] (element (m, k) at A[k * lda + m]); 2: B is stored [K][N]
+  int k_major;            // 0: both K-contiguous; 1: A is stored [K][M] (element (m, k) at A[k * lda + m]);
+                          // 2: B is stored [K][N]
   int k_rows;             // rows of the k-major operand that exist; K may round up beyond, the other
                           // operand must be zero there
 };

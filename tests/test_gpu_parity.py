@@ -187,6 +187,34 @@ def test_multi_teacher_and_tau2():
     G.check(b, ref, "tau^2")
 
 
+@pytest.mark.parametrize("name,kind,beta", KINDS)
+def test_heads_stored_hidden_major(name, kind, beta, monkeypatch):
+    """KD_W_HV: W_t [H_t, V], W_s [H_s, V] and grad_W_s [H_s, V], read and written in place.  Against the
+    oracle in the same storage order, and against the library's own [V, H] result."""
+    import torch
+    from oracle import kd_oracle as O
+    from paper_2603_01875_amd import kdloss as K
+    monkeypatch.setenv("KD_VOCAB_CHUNK", "512")
+    # 3 token tiles (ragged, masked tails), 13 vocabulary tiles (last one 64 rows), 4 chunks (last one 192 wide)
+    cfg = I.scaled(I.workload(name), batch=3, seq=200, H_t=192, H_s=128, V=1600)
+    data = I.generate(cfg)
+    hv = {k: np.ascontiguousarray(data[k].T) for k in ("W_t", "W_s")}
+    ref = O.kd_loss_fwd_bwd(data["h_t"], hv["W_t"], data["h_s"], hv["W_s"], data["mask"], cfg.tau, kind, beta, O.W_HV)
+    ref["per_token_loss"] = ref["per_token_loss"] * (data["mask"] != 0)
+    assert ref["grad_W_s"].shape == (cfg.H_s, cfg.V)
+    dev = lambda x: G.to_device(x, I.BF16)
+    mask = torch.from_numpy(data["mask"]).cuda()
+    out = K.kd_loss_fwd_bwd(dev(data["h_t"]), dev(hv["W_t"]), dev(data["h_s"]), dev(hv["W_s"]), mask, tau=cfg.tau,
+                            kind=kind, beta=beta, w_layout=K.W_HV)
+    torch.cuda.synchronize()
+    assert tuple(out["grad_W_s"].shape) == (cfg.H_s, cfg.V)
+    G.check(out, ref, name + " [H,V] heads")
+    vh = G.run_gpu(cfg, data)
+    assert float(out["loss"].item()) == pytest.approx(float(vh["loss"].item()), rel=1e-6)
+    assert torch.allclose(out["grad_W_s"].float().T, vh["grad_W_s"].float(), rtol=0, atol=1e-2 * vh["grad_W_s"].abs().max().item())
+    assert torch.allclose(out["grad_h_s"].float(), vh["grad_h_s"].float(), rtol=0, atol=1e-2 * vh["grad_h_s"].abs().max().item())
+
+
 def test_three_teachers_share_the_backward_products(monkeypatch):
     """Three teachers, several vocabulary chunks, no mask, fp32 gradients: every chunk of dL/dz_s is the
     weighted sum over the teachers before the two products run once."""
