@@ -36,3 +36,54 @@ def test_random_case(seed, monkeypatch):
     what = (f"seed={seed} T={cfg.T} H_t={cfg.H_t} H_s={cfg.H_s} V={cfg.V} kind={cfg.kind} tau={cfg.tau:.3f} "
             f"beta={cfg.beta:.2f} dtype={cfg.dtype} mask={cfg.mask} chunk={chunk}")
     G.check(out, G.run_oracle(cfg, data), what, extra)
+
+
+def _case_modes(seed):
+    """Shapes for the optional modes: [H,V] heads (sizes in whole 64-element steps) or the fp8 teacher
+    (H_t in whole 128-element steps)."""
+    rng = np.random.default_rng(3000 + seed)
+    mode = ("hv", "fp8")[seed % 2]
+    kind = int(rng.integers(0, 6))
+    cfg = I.KDConfig(
+        name=f"modes{seed}", batch=int(rng.integers(1, 4)), seq=int(rng.integers(1, 260)),
+        H_t=(64 if mode == "hv" else 128) * int(rng.integers(1, 5)),
+        H_s=64 * int(rng.integers(1, 4)) if mode == "hv" else 8 * int(rng.integers(1, 24)),
+        V=64 * int(rng.integers(1, 50)) if mode == "hv" else 8 * int(rng.integers(1, 400)),
+        dtype=I.BF16, w_t_std=float(rng.choice([0.02, 0.05, 0.2])), w_s_std=float(rng.choice([0.02, 0.06])),
+        rms_norm=bool(rng.integers(0, 2)), kind=kind, tau=float(np.exp(rng.uniform(np.log(0.3), np.log(5.0)))),
+        beta=float(rng.uniform(0.05, 0.95)), mask=str(rng.choice(["ones", "tail25", "bernoulli10"])), seed=7000 + seed)
+    return mode, cfg, int(rng.choice([256, 512, 1024, 16384]))
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_random_case_other_layout_or_fp8_teacher(seed, monkeypatch):
+    import torch
+    from oracle import kd_oracle as O
+    from paper_2603_01875_amd import kdloss as K
+    mode, cfg, chunk = _case_modes(seed)
+    monkeypatch.setenv("KD_VOCAB_CHUNK", str(chunk))
+    data = I.generate(cfg)
+    what = (f"{mode} seed={seed} T={cfg.T} H_t={cfg.H_t} H_s={cfg.H_s} V={cfg.V} kind={cfg.kind} tau={cfg.tau:.3f} "
+            f"beta={cfg.beta:.2f} mask={cfg.mask} chunk={chunk}")
+    dev = lambda x: G.to_device(x, I.BF16)
+    mask = torch.from_numpy(data["mask"]).cuda()
+    if mode == "hv":
+        hv = {k: np.ascontiguousarray(data[k].T) for k in ("W_t", "W_s")}
+        ref = O.kd_loss_fwd_bwd(data["h_t"], hv["W_t"], data["h_s"], hv["W_s"], data["mask"], cfg.tau, cfg.kind,
+                                cfg.beta, O.W_HV)
+        ref["per_token_loss"] = ref["per_token_loss"] * (data["mask"] != 0)
+        out = K.kd_loss_fwd_bwd(dev(data["h_t"]), dev(hv["W_t"]), dev(data["h_s"]), dev(hv["W_s"]), mask,
+                                tau=cfg.tau, kind=cfg.kind, beta=cfg.beta, w_layout=K.W_HV)
+        d = data
+    else:
+        f8 = I.fp8_teacher(data)
+        d = dict(data); d["h_t"], d["W_t"] = f8["h_t"], f8["W_t"]
+        ref = G.run_oracle(cfg, d)
+        out = K.kd_loss_fwd_bwd(torch.from_numpy(f8["q_h_t"]).cuda(), torch.from_numpy(f8["q_W_t"]).cuda(),
+                                dev(data["h_s"]), dev(data["W_s"]), mask, tau=cfg.tau, kind=cfg.kind, beta=cfg.beta,
+                                flags=K.FLAG_TEACHER_FP8, teacher_scale=f8["teacher_scale"])
+    torch.cuda.synchronize()
+    extra = G.tvd_tie_allowance(cfg, d) if cfg.kind == I.TVD else None
+    if extra is not None and mode == "hv":
+        extra = dict(grad_h_s=extra["grad_h_s"], grad_W_s=extra["grad_W_s"].T)
+    G.check(out, ref, what, extra)
