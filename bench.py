@@ -110,14 +110,18 @@ def main():
     # timed region: exactly `steps` steps, bracketed by synchronisation; the dominant kernel
     # (logit tiles + online log-sum-exp, one launch per step) is bracketed by events inside it
     kt = K.KernelTimer(K.PROF_STATS, args.steps)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     with kt:
-        for _ in range(args.steps):
+        marks[0].record()
+        for i in range(args.steps):
             step()
+            marks[i + 1].record()          # per-step durations for the median / minimum (same stream)
         torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     stats_ms = kt.durations_ms()
     stats_avg = sum(stats_ms) / len(stats_ms)
 
@@ -174,6 +178,7 @@ def main():
         "tflops_executed": flop_exec / (ms_per_step * 1e-3) / 1e12,
         "mfma_frac_whole_step": (flop_exec / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS if not args.teacher_fp8 else
                                  (flop_exec - passes * 2.0 * T_comp * V * H_t / 2) / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS),
+        "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
         "kernel_ms": dict(stats=stats_avg, **fam),
         "workspace_bytes": int(ws.numel()), "two_T_V_bytes": 2 * T * V,
         "loss": float(loss.item()),
