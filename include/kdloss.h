@@ -28,7 +28,9 @@
  *  - all argument checks run on the host before anything touches the GPU, so
  *    they can be exercised on a machine without one.
  *  - work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
- *    the default stream) and the call returns without waiting.
+ *    the default stream) and the call returns without waiting.  Only kernels are
+ *    enqueued (no memsets, no copies), so a call may be captured into a HIP graph;
+ *    the workspace carries nothing from one call to the next.
  */
 #ifndef KDLOSS_H
 #define KDLOSS_H
