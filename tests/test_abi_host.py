@@ -26,6 +26,14 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(L, n), n
 
 
+def test_header_is_plain_c():
+    """The boundary is a C ABI: the header must compile as C99 on its own."""
+    import subprocess
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-x", "c",
+                        os.path.join(ROOT, "include", "kdloss.h")], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+
+
 def test_struct_layout_matches_header():
     assert ctypes.sizeof(K.KdLossParams) == 4 * 8 + 10 * 4          # 72 bytes, no padding
 

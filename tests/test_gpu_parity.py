@@ -252,3 +252,24 @@ def test_ragged_last_tile_with_high_temperature(kind, beta, tau):
     data = I.generate(cfg)
     extra = G.tvd_tie_allowance(cfg, data) if kind == I.TVD else None
     G.check(G.run_gpu(cfg, data), G.run_oracle(cfg, data), f"kind={kind} tau={tau}", extra)
+
+
+def test_autograd_front_end():
+    """loss.backward() through the torch.autograd wrapper delivers the library's gradients, scaled by the
+    incoming gradient; compared with the oracle."""
+    import torch
+    from paper_2603_01875_amd.autograd import kd_loss
+    cfg = I.scaled(I.workload("rkl_bf16"), batch=2, seq=130, H_t=128, H_s=64, V=904)
+    data = I.generate(cfg)
+    dev = lambda x: G.to_device(x, I.BF16)
+    h_s = dev(data["h_s"]).requires_grad_(True)
+    W_s = dev(data["W_s"]).requires_grad_(True)
+    mask = torch.from_numpy(data["mask"]).cuda()
+    loss = kd_loss(h_s, W_s, dev(data["h_t"]), dev(data["W_t"]), mask, tau=cfg.tau, kind=cfg.kind, beta=cfg.beta)
+    (3.0 * loss).backward()
+    torch.cuda.synchronize()
+    ref = G.run_oracle(cfg, data)
+    assert abs(float(loss.item()) - ref["loss"]) <= G.LOSS_RTOL * abs(ref["loss"])
+    for t, name in ((h_s, "grad_h_s"), (W_s, "grad_W_s")):
+        g = G.to_host(t.grad)
+        assert np.abs(g - 3.0 * ref[name]).max() <= G.GRAD_TOL * np.abs(3.0 * ref[name]).max() * 1.5, name
