@@ -83,15 +83,22 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward, si
   // enough to keep every CU busy with up to half of the tokens masked.
   int ns = 2 * ((q.n_cu + q.n_tt - 1) / q.n_tt);
   if (ns < 8) ns = 8;
-  if (ns > 32) ns = 32;
+  if (ns > q.n_cu) ns = q.n_cu;          // a single token tile is split over all CUs
   if (ns > q.n_vt) ns = q.n_vt;
   if (ns < 1) ns = 1;
   q.n_split = ns;
 
-  // vocabulary chunk of the backward pass: the largest power of two (1024..16384 columns)
-  // whose [T_pad, V_c] bf16 staging buffer stays within 512 MiB
-  int64_t vc = 16384;
-  while (vc > 1024 && (int64_t)q.T_pad * vc * 2 > (512ll << 20)) vc >>= 1;
+  // vocabulary chunk of the backward pass: a power of two.  The [T_pad, V_c] bf16 staging buffer of
+  // dL/dz_s is written by the gradient kernel and read back by both products, so it should stay within
+  // the 256 MB last-level cache together with the operands (128 MiB: measured best from T = 256 to 4096);
+  // but every chunk also re-reads and re-writes the fp32 sums of grad_h_s, so with many tokens a chunk
+  // of at least 8192 columns wins as long as the staging buffer stays within 512 MiB.
+  int64_t vc = 1 << 20;
+  while (vc > 1024 && (int64_t)q.T_pad * vc * 2 > (128ll << 20)) vc >>= 1;
+  if (vc < 8192) {
+    vc = 8192;
+    while (vc > 1024 && (int64_t)q.T_pad * vc * 2 > (512ll << 20)) vc >>= 1;
+  }
   if (const char* e = std::getenv("KD_VOCAB_CHUNK")) {
     const long v = std::atol(e);
     if (v >= 256 && v <= (1 << 20)) vc = round_up(v, 256);
@@ -104,7 +111,7 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward, si
   const int tiles_h = ((q.H_s + kd::kGemmTileM - 1) / kd::kGemmTileM) * q.n_tt;
   int sk = q.n_cu / tiles_h;
   if (sk < 1) sk = 1;
-  if (sk > 8) sk = 8;
+  if (sk > 32) sk = 32;
   while (sk > 1 && q.V_c / sk < 512) --sk;
   const int steps_first = (int)(round_up(q.V < q.V_c ? q.V : q.V_c, 64) / 64);
   if (sk > steps_first) sk = steps_first;
