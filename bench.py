@@ -45,7 +45,7 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="fkl_bf16")
-    ap.add_argument("--cpu-rows", type=int, default=64, help="tokens of the oracle sample (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=1024, help="tokens of the oracle sample (0 = skip)")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "traffic.json"))
     ap.add_argument("--teacher-fp8", action="store_true",
                     help="optional mode, not the headline: teacher hidden states and head quantised to e4m3 "
