@@ -85,53 +85,6 @@ def bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (b.astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
-def e4m3_values() -> np.ndarray:
-    """The 256 values of the OCP e4m3 byte codes (sign, 4 exponent bits with bias 7, 3 mantissa
-    bits; no infinities; 0x7f and 0xff are NaN), as float64."""
-    c = np.arange(256)
-    e, m = (c >> 3) & 15, c & 7
-    v = np.where(e == 0, m * 2.0 ** -9, (1.0 + m / 8.0) * 2.0 ** (e.astype(np.float64) - 7))
-    v[(e == 15) & (m == 7)] = np.nan
-    return np.where(c & 128, -v, v)
-
-
-def quantize_e4m3(x: np.ndarray, scale: float) -> np.ndarray:
-    """uint8 e4m3 codes of x * (1 / scale), the reciprocal and the product in fp32: nearest
-    representable value, ties to the even code, magnitudes beyond 448 saturate, NaN -> 0x7f | sign.
-    Written as a search over the value table, not as bit manipulation."""
-    x = np.asarray(x, dtype=np.float32)
-    inv = np.float32(1.0) / np.float32(scale)
-    pos = e4m3_values()[:127]                       # codes 0x00..0x7e: 0 .. 448, increasing
-    out = np.empty(x.shape, dtype=np.uint8)
-    xf, of = x.reshape(-1), out.reshape(-1)
-    for i0 in range(0, xf.size, 1 << 24):           # blocks only bound the temporaries
-        y = (xf[i0:i0 + (1 << 24)] * inv).astype(np.float32)
-        a = np.abs(y).astype(np.float64)
-        hi = np.clip(np.searchsorted(pos, a, side="left"), 1, 126)
-        lo = hi - 1
-        d_lo, d_hi = a - pos[lo], pos[hi] - a
-        code = np.where(d_lo < d_hi, lo, np.where(d_hi < d_lo, hi, np.where(lo % 2 == 0, lo, hi)))
-        code = np.where(a >= 448.0, 126, code)
-        code = np.where(np.isnan(a), 127, code)
-        of[i0:i0 + (1 << 24)] = (code | np.where(np.signbit(y), 128, 0)).astype(np.uint8)
-    return out
-
-
-def fp8_teacher(data: dict) -> dict:
-    """The teacher side of `data` quantised to e4m3 with one scale per array (max|x| / 448).
-    Returns the codes (for the GPU), the scales, and the de-quantised arrays (for the oracle)."""
-    tab = e4m3_values()
-    out = {}
-    for k in ("h_t", "W_t"):
-        s = float(np.float32(np.abs(data[k]).max() / 448.0))
-        q = quantize_e4m3(data[k], s)
-        out["q_" + k], out["scale_" + k] = q, s
-        out[k] = (tab[q] * np.float64(np.float32(s))).astype(np.float64)
-    # the kernels apply the product of the two scales as one fp32 factor
-    out["teacher_scale"] = float(np.float32(out["scale_h_t"]) * np.float32(out["scale_W_t"]))
-    return out
-
-
 def _hidden(rng, T, H, rms_norm, dtype):
     h = rng.standard_normal((T, H), dtype=np.float32)
     if rms_norm:

@@ -2,6 +2,7 @@
 its C ABI, run the fp64 oracle on the same arrays, compare."""
 import numpy as np
 
+from oracle import e4m3 as E
 from oracle import kd_oracle as O
 from paper_2603_01875_amd import inputs as I
 
@@ -10,6 +11,21 @@ GRAD_TOL = 2e-2           # gradient max-abs error, as a fraction of the oracle'
 
 
 to_device = I.to_device
+
+
+def fp8_teacher(data: dict) -> dict:
+    """The teacher side of `data` quantised to e4m3 with one scale per array (max|x| / 448).
+    Returns the codes (for the GPU), the scales, and the de-quantised arrays (for the oracle)."""
+    tab = E.e4m3_values()
+    out = {}
+    for k in ("h_t", "W_t"):
+        s = float(np.float32(np.abs(data[k]).max() / 448.0))
+        q = E.quantize_e4m3(data[k], s)
+        out["q_" + k], out["scale_" + k] = q, s
+        out[k] = (tab[q] * np.float64(np.float32(s))).astype(np.float64)
+    # the kernels apply the product of the two scales as one fp32 factor
+    out["teacher_scale"] = float(np.float32(out["scale_h_t"]) * np.float32(out["scale_W_t"]))
+    return out
 
 
 def to_host(t):

@@ -10,6 +10,7 @@ import pytest
 
 from oracle import kd_oracle as O
 from paper_2603_01875_amd import inputs as I
+from tests import gpu_util as G
 
 
 def _rel(a, b):
@@ -28,7 +29,7 @@ def test_fp8_teacher_changes_loss_and_gradients_little(name, kind, beta, loss_to
     w = I.workload(name)
     cfg = I.scaled(w, batch=1, seq=96, V=4096, H_t=min(w.H_t, 2048), H_s=min(w.H_s, 512), mask="ones")
     data = I.generate(cfg)
-    f8 = I.fp8_teacher(data)
+    f8 = G.fp8_teacher(data)
     ref = O.kd_loss_fwd_bwd(data["h_t"], data["W_t"], data["h_s"], data["W_s"], None, cfg.tau, kind, beta, O.W_VH)
     q = O.kd_loss_fwd_bwd(f8["h_t"], f8["W_t"], data["h_s"], data["W_s"], None, cfg.tau, kind, beta, O.W_VH)
     dl = abs(q["loss"] - ref["loss"]) / ref["loss"]

@@ -5,6 +5,7 @@ so the tolerances are the ones of the bf16 path.  The quantiser kernel is checke
 import numpy as np
 import pytest
 
+from oracle import e4m3 as E
 from paper_2603_01875_amd import inputs as I
 from tests import gpu_util as G
 
@@ -51,7 +52,7 @@ def test_quantiser_is_bit_exact(src):
         xd = xd.to(torch.bfloat16)
     for scale in (1.0, 0.37, 3.0e-3):
         got = K.quantize_e4m3(xd, scale).cpu().numpy()
-        want = I.quantize_e4m3(x, scale)
+        want = E.quantize_e4m3(x, scale)
         np.testing.assert_array_equal(got, want)
 
 
@@ -64,7 +65,7 @@ def test_fp8_teacher_ragged_multi_tile(name, kind, beta, monkeypatch):
     monkeypatch.setenv("KD_VOCAB_CHUNK", "512")
     cfg = I.scaled(I.workload(name), batch=3, seq=200, H_t=384, H_s=128, V=2440)
     data = I.generate(cfg)
-    f8 = I.fp8_teacher(data)
+    f8 = G.fp8_teacher(data)
     out = _run_fp8(cfg, data, f8)
     G.check(out, _oracle_fp8(cfg, data, f8), name + " fp8 teacher")
     keep = data["mask"].astype(bool)
@@ -75,7 +76,7 @@ def test_fp8_teacher_ragged_multi_tile(name, kind, beta, monkeypatch):
 def test_fp8_teacher_other_divergences(kind, beta):
     cfg = I.scaled(I.workload("fkl_bf16"), batch=2, seq=150, H_t=128, H_s=64, V=1000, kind=kind, beta=beta)
     data = I.generate(cfg)
-    f8 = I.fp8_teacher(data)
+    f8 = G.fp8_teacher(data)
     d = dict(data); d["h_t"], d["W_t"] = f8["h_t"], f8["W_t"]
     extra = G.tvd_tie_allowance(cfg, d) if kind == I.TVD else None
     G.check(_run_fp8(cfg, data, f8), _oracle_fp8(cfg, data, f8), f"kind {kind} fp8 teacher", extra)
@@ -85,14 +86,14 @@ def test_fp8_teacher_other_divergences(kind, beta):
 def test_fp8_teacher_hidden_sizes_and_temperature(H_t):
     cfg = I.scaled(I.workload("fkl_bf16"), batch=1, seq=300, H_t=H_t, H_s=64, V=776, tau=2.5, mask="ones")
     data = I.generate(cfg)
-    f8 = I.fp8_teacher(data)
+    f8 = G.fp8_teacher(data)
     G.check(_run_fp8(cfg, data, f8), _oracle_fp8(cfg, data, f8), f"H_t={H_t} fp8 teacher")
 
 
 def test_fp8_teacher_forward_only_matches_full_call():
     cfg = I.scaled(I.workload("jsd_bf16"), batch=2, seq=160, H_t=256, H_s=128, V=1288)
     data = I.generate(cfg)
-    f8 = I.fp8_teacher(data)
+    f8 = G.fp8_teacher(data)
     full = _run_fp8(cfg, data, f8)
     fwd = _run_fp8(cfg, data, f8, forward_only=True)
     assert float(full["loss"].item()) == float(fwd["loss"].item())
@@ -105,15 +106,15 @@ def test_codes_that_bf16_holds_exactly_give_the_bf16_result():
     import torch
     cfg = I.scaled(I.workload("fkl_bf16"), batch=2, seq=140, H_t=256, H_s=64, V=1000)
     data = I.generate(cfg)
-    f8 = I.fp8_teacher(data)
+    f8 = G.fp8_teacher(data)
     a = _run_fp8(cfg, data, f8)
     # power-of-two scales keep the de-quantised values bf16-exact: re-quantise with such scales
     d = dict(data)
-    tab = I.e4m3_values()
+    tab = E.e4m3_values()
     q = {}
     for k in ("h_t", "W_t"):
         s = float(2.0 ** np.ceil(np.log2(np.abs(data[k]).max() / 448.0)))
-        q[k] = (I.quantize_e4m3(data[k], s), s)
+        q[k] = (E.quantize_e4m3(data[k], s), s)
         d[k] = (tab[q[k][0]] * s).astype(np.float32)
         assert (I.round_to_bf16(d[k]) == d[k]).all()
     f8p = dict(q_h_t=q["h_t"][0], q_W_t=q["W_t"][0], teacher_scale=q["h_t"][1] * q["W_t"][1])

@@ -122,7 +122,7 @@ def test_headline_workload_with_fp8_teacher():
     from paper_2603_01875_amd import kdloss as K
     cfg = I.workload("fkl_bf16")
     data = I.generate(cfg)
-    f8 = I.fp8_teacher(data)
+    f8 = G.fp8_teacher(data)
     out = K.kd_loss_fwd_bwd(torch.from_numpy(f8["q_h_t"]).cuda(), torch.from_numpy(f8["q_W_t"]).cuda(),
                             G.to_device(data["h_s"], cfg.dtype), G.to_device(data["W_s"], cfg.dtype),
                             torch.from_numpy(data["mask"]).cuda(), tau=cfg.tau, kind=cfg.kind, beta=cfg.beta,

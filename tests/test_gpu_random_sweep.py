@@ -76,7 +76,7 @@ def test_random_case_other_layout_or_fp8_teacher(seed, monkeypatch):
                                 tau=cfg.tau, kind=cfg.kind, beta=cfg.beta, w_layout=K.W_HV)
         d = data
     else:
-        f8 = I.fp8_teacher(data)
+        f8 = G.fp8_teacher(data)
         d = dict(data); d["h_t"], d["W_t"] = f8["h_t"], f8["W_t"]
         ref = G.run_oracle(cfg, d)
         out = K.kd_loss_fwd_bwd(torch.from_numpy(f8["q_h_t"]).cuda(), torch.from_numpy(f8["q_W_t"]).cuda(),
