@@ -273,3 +273,15 @@ def test_autograd_front_end():
     for t, name in ((h_s, "grad_h_s"), (W_s, "grad_W_s")):
         g = G.to_host(t.grad)
         assert np.abs(g - 3.0 * ref[name]).max() <= G.GRAD_TOL * np.abs(3.0 * ref[name]).max() * 1.5, name
+
+
+@pytest.mark.parametrize("T", [7, 100, 300, 700])
+@pytest.mark.parametrize("name,kind,beta", KINDS[:3])
+def test_few_tokens_large_vocabulary(name, kind, beta, T):
+    """Few token tiles and a long vocabulary: the statistics passes split the vocabulary over up to one
+    workgroup per CU, the backward pass takes the whole vocabulary as one chunk and the grad_h_s product
+    splits its contraction up to 32 ways."""
+    cfg = I.scaled(I.workload(name), batch=1, seq=T, H_t=256, H_s=128, V=40008)
+    data = I.generate(cfg)
+    out = G.run_gpu(cfg, data)
+    G.check(out, G.run_oracle(cfg, data), f"{name} T={T}")
