@@ -284,17 +284,21 @@ struct RowTerm {
     }
     const float wt = (KIND == 5) ? 1.f - w : w;          // weight of p_t in the mixture
     const float M = fmaf(wt, pt, (1.f - wt) * ps);
-    const float lm = M > 0.f ? flog2(M) : 0.f;           // M == 0 only where p_t = p_s = 0
+    // The hardware logarithm takes subnormal arguments for zero (-inf, and inf * 0 further on): a
+    // mixture below the smallest normal number counts as absent, like an exact zero (p_t = p_s = 0);
+    // what it would contribute is below 1e-36.
+    const bool live = M >= 1.17549435e-38f;
+    const float lm = live ? flog2(M) : 0.f;
     if (KIND == 2) {
       if (ACC) { a1 = fmaf(pt, lt - lm, a1); a2 = fmaf(ps, ls - lm, a2); }
       return (1.f - w) * LN2 * (ls - lm);
     }
     if (KIND == 4) {
-      const float r = M > 0.f ? fexp2(lt - lm) : 0.f;    // p_t / M
+      const float r = live ? fexp2(lt - lm) : 0.f;       // p_t / M
       if (ACC) { a1 = fmaf(pt, lt - lm, a1); a2 = fmaf(ps, r, a2); }
       return -(1.f - w) * r;
     }
-    const float r = M > 0.f ? fexp2(ls - lm) : 0.f;      // p_s / M
+    const float r = live ? fexp2(ls - lm) : 0.f;         // p_s / M
     const float cc = fmaf(LN2, ls - lm, 1.f - w * r);
     if (ACC) { a1 = fmaf(ps, ls - lm, a1); a2 = fmaf(ps, cc, a2); }
     return cc;
