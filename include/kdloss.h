@@ -89,7 +89,10 @@ typedef struct {
   int32_t grad_dtype;   /* kd_dtype of grad_h_s and grad_W_s                        */
   int32_t w_layout;     /* kd_wlayout                                               */
   int32_t kind;         /* kd_kind                                                  */
-  float tau;            /* temperature, 1e-6 <= tau <= 1e6                          */
+  float tau;            /* temperature, 1e-6 <= tau <= 1e6.  The scaled logits z / tau
+                           are held in fp32: results are meaningful while |z| / tau
+                           stays below about 1e5, and a loss far below 1e-4 (very
+                           high temperatures) is resolved to about 1e-7 absolute    */
   float beta;           /* JSD mixing weight on the teacher term, or the skew weight
                            of the skewed KLs; 0 < beta < 1; ignored for FKL/RKL/TVD */
   int32_t accumulate_grad_W; /* 0: grad_W_s is overwritten. 1: added to (gradient
