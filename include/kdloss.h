@@ -178,8 +178,9 @@ kd_status kd_loss_fwd_bwd_multi(const kd_loss_params* params, int n_teachers,
 /* Static, NUL-terminated description of a status code. */
 const char* kd_status_string(kd_status status);
 
-/* Number of kernels the last plan for these params launches and the vocabulary
- * chunk it uses; for reports.  Either output pointer may be NULL. */
+/* For reports: the vocabulary chunk kd_loss_fwd_bwd uses for these params and the number of kernels
+ * one call launches (counted as for a call with a mask, whose hidden states are compacted into the
+ * workspace).  Either output pointer may be NULL.  Host only. */
 kd_status kd_loss_plan_info(const kd_loss_params* params, int64_t* vocab_chunk,
                             int64_t* n_launches);
 

@@ -348,7 +348,11 @@ kd_status kd_loss_plan_info(const kd_loss_params* params, int64_t* vocab_chunk, 
   plan(params, q, L, true);
   const int64_t chunks = (q.V + q.V_c - 1) / q.V_c;
   if (vocab_chunk) *vocab_chunk = q.V_c;
-  if (n_launches) *n_launches = 6 + (q.kind >= KD_JSD ? 2 : 0) + 1 + chunks * 4 + 1;
+  // compaction, operand copies (as with a mask), statistics + merge, row pass + merge, loss,
+  // h_s^T, per chunk the gradient kernel and the two products, grad_h_s conversion
+  if (n_launches)
+    *n_launches = 1 + (q.prep_ht + q.prep_Wt + q.prep_hs + q.prep_Ws) + 2 + (q.kind >= KD_JSD ? 2 : 0) + 1 + 1 +
+                  chunks * 3 + 1;
   return KD_OK;
 }
 
