@@ -192,9 +192,9 @@ kd_status kd_loss_plan_info(const kd_loss_params* params, int64_t* vocab_chunk,
  * `events` is a host array of hipEvent_t owned by the caller, which must outlive the
  * hook.  which < 0 clears the hook.  Host only; touches no device memory. */
 typedef enum {
-  KD_PROF_STATS = 0,        /* logit tiles + online log-sum-exp (one launch per call)   */
-  KD_PROF_ROWS = 1,         /* row pass of JSD / TVD / skewed KL (one launch per call)  */
-  KD_PROF_GRAD = 2,         /* logit tiles + dL/dz_s epilogue (one launch per chunk)    */
+  KD_PROF_STATS = 0,        /* logit tiles + online log-sum-exp (one launch per teacher) */
+  KD_PROF_ROWS = 1,         /* row pass of JSD / TVD / skewed KL (one launch per teacher) */
+  KD_PROF_GRAD = 2,         /* logit tiles + dL/dz_s epilogue (one launch per chunk and teacher) */
   KD_PROF_GEMM_GRAD_W = 3,  /* grad_W_s product (one launch per chunk)                  */
   KD_PROF_GEMM_GRAD_H = 4   /* grad_h_s product (one launch per chunk)                  */
 } kd_prof_kernel;
