@@ -59,8 +59,13 @@ def test_workspace_is_far_below_T_times_V():
     p5 = K.make_params(32768, 5120, 4096, 151936, kind=K.JSD, beta=0.1)
     n5 = K.kd_loss_workspace_size(p5)
     assert n5 < 0.3 * 2 * 32768 * 151936           # dz chunk copies, fp32 grad_h_s sums, compact hidden copies
-    # the footnote's full-logit volume (128 x 4096 x 151936 bf16) is ~160 GB; ours is ~1000x smaller
-    assert 128 * 4096 * 151936 * 2 / n > 300
+    # the full-logit volume the paper quotes (footnote of Sec. 1, kept in tests/golden) against what this
+    # library needs for the same number of tokens processed one 4096-token batch at a time
+    seqs, toks, vocab, width, approx_gb = [int(x) for x in
+        [l for l in open(os.path.join(ROOT, "tests", "golden", "full_logit_volume.txt")) if l[0] != "#"][0].split()]
+    full = seqs * toks * vocab * width
+    assert abs(full / 1e9 - approx_gb) < 0.01 * approx_gb and vocab == 151936
+    assert full / n > 300
 
 
 @pytest.mark.parametrize("kw,status", [
