@@ -78,7 +78,8 @@ typedef enum { KD_W_HV = 0, KD_W_VH = 1 } kd_wlayout;
  * teacher_scale = scale_h * scale_W.  The teacher logit tiles then run on the fp8 matrix pipe at twice the
  * bf16 rate and half the operand traffic; everything else (student side, divergence, gradients) is unchanged.
  * An extension in the spirit of the paper's FP8 teacher inference (Table 3): the paper does not quantise the
- * head.  Requires in_dtype == KD_BF16 and H_t a multiple of 128; not available in the multi-teacher call. */
+ * head.  Requires in_dtype == KD_BF16, w_layout == KD_W_VH and H_t a multiple of 128.  In the multi-teacher
+ * call every teacher is then fp8, each with its own scale (teacher_scales[k]; params->teacher_scale is not read). */
 typedef enum { KD_FLAG_TAU2 = 1, KD_FLAG_TEACHER_FP8 = 2 } kd_flags;
 
 typedef struct {
@@ -159,8 +160,9 @@ kd_status kd_quantize_e4m3(const void* src, int32_t src_dtype, int64_t n, float 
 /* Multi-teacher distillation (Table 1, "Multi-Teacher Distillation"): n_teachers teachers over the
  * same tokens and vocabulary, each with its own hidden states h_t[k] [T, H_t[k]] and head W_t[k];
  *   loss = sum_k weights[k] * D(p_t^k, p_s)      (same divergence, temperature and mask for all)
- * and the gradients are those of that sum.  params->H_t is ignored; h_t, W_t, H_t, weights are HOST
- * arrays of n_teachers entries (the pointers in h_t / W_t are device pointers).  1 <= n_teachers <= 16.
+ * and the gradients are those of that sum.  params->H_t is ignored; h_t, W_t, H_t, weights (and
+ * teacher_scales, read only with KD_FLAG_TEACHER_FP8, else may be NULL) are HOST arrays of n_teachers
+ * entries (the pointers in h_t / W_t are device pointers).  1 <= n_teachers <= 16.
  * Everything else is as for kd_loss_fwd_bwd; the workspace must satisfy the _multi size query (the
  * single-teacher workspace plus, per teacher, its row statistics and any re-packed operand copies).
  * The token compaction, the student operands and the two backward products are shared: each chunk of
@@ -170,7 +172,7 @@ kd_status kd_loss_workspace_size_multi(const kd_loss_params* params, int n_teach
                                        size_t* bytes);
 kd_status kd_loss_fwd_bwd_multi(const kd_loss_params* params, int n_teachers,
                                 const void* const* h_t, const void* const* W_t, const int64_t* H_t,
-                                const float* weights,
+                                const float* weights, const float* teacher_scales,
                                 const void* h_s, const void* W_s, const uint8_t* mask,
                                 float* loss, float* per_token_loss, void* grad_h_s, void* grad_W_s,
                                 void* workspace, size_t workspace_bytes, void* hip_stream);

@@ -389,11 +389,11 @@ kd_status kd_loss_workspace_size_multi(const kd_loss_params* params, int n_teach
                                        size_t* bytes) {
   if (!bytes || !params || !H_t) return KD_ERR_NULL;
   if (n_teachers < 1 || n_teachers > 16) return KD_ERR_PARAM;
-  if (params->flags & KD_FLAG_TEACHER_FP8) return KD_ERR_UNSUPPORTED;   // one scale cannot serve several teachers
   size_t base = 0;                       // teacher blocks lie side by side after the common part
   for (int k = 0; k < n_teachers; ++k) {
     kd_loss_params pk = *params;
     pk.H_t = H_t[k];
+    if (pk.flags & KD_FLAG_TEACHER_FP8) pk.teacher_scale = 1.f;   // the size does not depend on the scales
     kd_status s = check_params(&pk);
     if (s != KD_OK) return s;
     Problem q{};
@@ -407,12 +407,14 @@ kd_status kd_loss_workspace_size_multi(const kd_loss_params* params, int n_teach
 
 kd_status kd_loss_fwd_bwd_multi(const kd_loss_params* params, int n_teachers, const void* const* h_t,
                                 const void* const* W_t, const int64_t* H_t, const float* weights,
+                                const float* teacher_scales,
                                 const void* h_s, const void* W_s, const uint8_t* mask, float* loss,
                                 float* per_token_loss, void* grad_h_s, void* grad_W_s, void* workspace,
                                 size_t workspace_bytes, void* hip_stream) {
   if (!params || !h_t || !W_t || !H_t || !weights) return KD_ERR_NULL;
   if (n_teachers < 1 || n_teachers > 16) return KD_ERR_PARAM;
-  if (params->flags & KD_FLAG_TEACHER_FP8) return KD_ERR_UNSUPPORTED;
+  const bool fp8 = (params->flags & KD_FLAG_TEACHER_FP8) != 0;
+  if (fp8 && !teacher_scales) return KD_ERR_NULL;
   // all checks for all teachers before the first launch
   Problem q[16];
   Layout L[16];
@@ -421,6 +423,7 @@ kd_status kd_loss_fwd_bwd_multi(const kd_loss_params* params, int n_teachers, co
     if (!std::isfinite(weights[k])) return KD_ERR_PARAM;
     kd_loss_params pk = *params;
     pk.H_t = H_t[k];
+    if (fp8) pk.teacher_scale = teacher_scales[k];
     q[k] = Problem{};
     kd_status s = check_buffers(&pk, h_t[k], W_t[k], h_s, W_s, mask, loss, workspace, workspace_bytes, true,
                                 grad_h_s, grad_W_s, q[k], L[k], base);

@@ -61,6 +61,7 @@ def lib():
         L.kd_loss_workspace_size_multi.restype = ctypes.c_int
         L.kd_loss_fwd_bwd_multi.argtypes = [P, ctypes.c_int, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                             ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_float),
+                                            ctypes.POINTER(ctypes.c_float),
                                             vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.kd_loss_fwd_bwd_multi.restype = ctypes.c_int
         L.kd_quantize_e4m3.argtypes = [vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, vp, vp]
@@ -237,8 +238,9 @@ def kd_loss_fwd_bwd(h_t, W_t, h_s, W_s, mask=None, tau=1.0, kind=FKL, beta=0.5, 
 
 
 def kd_loss_fwd_bwd_multi(h_ts, W_ts, weights, h_s, W_s, mask=None, tau=1.0, kind=FKL, beta=0.5, flags=0,
-                          grad_dtype=None):
-    """Multi-teacher call: lists of teacher hidden states / heads ([V,H] order) and weights."""
+                          grad_dtype=None, teacher_scales=None):
+    """Multi-teacher call: lists of teacher hidden states / heads ([V,H] order) and weights; with
+    FLAG_TEACHER_FP8 the teacher tensors are e4m3 codes and teacher_scales their joint scales."""
     import torch
     n = len(h_ts)
     in_dtype = BF16 if h_s.dtype == torch.bfloat16 else F32
@@ -262,7 +264,8 @@ def kd_loss_fwd_bwd_multi(h_ts, W_ts, weights, h_s, W_s, mask=None, tau=1.0, kin
     hp = (ctypes.c_void_p * n)(*[h.data_ptr() for h in h_ts])
     wp = (ctypes.c_void_p * n)(*[w.data_ptr() for w in W_ts])
     wt = (ctypes.c_float * n)(*[float(w) for w in weights])
-    st = lib().kd_loss_fwd_bwd_multi(ctypes.byref(p), n, hp, wp, H_t, wt, _ptr(h_s), _ptr(W_s), _ptr(mask),
+    sc = None if teacher_scales is None else (ctypes.c_float * n)(*[float(x) for x in teacher_scales])
+    st = lib().kd_loss_fwd_bwd_multi(ctypes.byref(p), n, hp, wp, H_t, wt, sc, _ptr(h_s), _ptr(W_s), _ptr(mask),
                                      _ptr(loss), _ptr(ptl), _ptr(grad_h), _ptr(grad_W), _ptr(ws),
                                      ctypes.c_size_t(ws.numel()),
                                      ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))

@@ -129,11 +129,15 @@ def test_fp8_teacher_params_and_workspace():
     bf = K.kd_loss_workspace_size(_ws())
     f8 = K.kd_loss_workspace_size(_ws(flags=K.FLAG_TEACHER_FP8, teacher_scale=1e-4))
     assert f8 < bf                                  # the compacted teacher hidden states are half the size
-    # one scale cannot describe several teachers
-    p = _ws(flags=K.FLAG_TEACHER_FP8, teacher_scale=1e-4)
-    H = (ctypes.c_int64 * 2)(4096, 4096)
+    # several fp8 teachers: the size query needs no scales, the call itself does
+    p = _ws(flags=K.FLAG_TEACHER_FP8)
+    H = (ctypes.c_int64 * 2)(4096, 2048)
     n = ctypes.c_size_t(0)
-    assert K.lib().kd_loss_workspace_size_multi(ctypes.byref(p), 2, H, ctypes.byref(n)) == 6
+    assert K.lib().kd_loss_workspace_size_multi(ctypes.byref(p), 2, H, ctypes.byref(n)) == 0 and n.value > f8
+    ptrs = (ctypes.c_void_p * 2)(0x1000, 0x2000)
+    w = (ctypes.c_float * 2)(0.5, 0.5)
+    g = [ctypes.c_void_p(0x1000 * (i + 3)) for i in range(8)]
+    assert K.lib().kd_loss_fwd_bwd_multi(ctypes.byref(p), 2, ptrs, ptrs, H, w, None, *g, ctypes.c_size_t(n.value), None) == 1
 
 
 def test_quantize_argument_checks():

@@ -124,3 +124,28 @@ def test_codes_that_bf16_holds_exactly_give_the_bf16_result():
     assert abs(la - lb) <= 1e-5 * abs(lb)
     ga, gb = G.to_host(a["grad_W_s"]), G.to_host(b["grad_W_s"])
     assert np.abs(ga - gb).max() <= 2e-2 * np.abs(gb).max()
+
+
+def test_two_fp8_teachers_with_their_own_scales(monkeypatch):
+    """Multi-teacher call with fp8 teachers: each teacher has its own joint scale; against the oracle on
+    the de-quantised teachers."""
+    import torch
+    from oracle import kd_oracle as O
+    from paper_2603_01875_amd import kdloss as K
+    monkeypatch.setenv("KD_VOCAB_CHUNK", "512")
+    base = I.scaled(I.workload("fkl_bf16"), batch=2, seq=150, H_s=128, V=1544)
+    ds = [I.generate(I.scaled(base, H_t=h, w_t_std=sd, seed=900 + i)) for i, (h, sd) in enumerate(((128, 0.02), (256, 0.05)))]
+    f8 = [G.fp8_teacher(d) for d in ds]
+    weights = (0.4, 0.6)
+    h_s, W_s, mask = ds[0]["h_s"], ds[0]["W_s"], ds[0]["mask"]
+    for kind, beta in ((I.FKL, 0.5), (I.JSD, 0.3)):
+        ref = O.kd_loss_multi([f["h_t"] for f in f8], [f["W_t"] for f in f8], weights, h_s, W_s, mask, base.tau,
+                              kind, beta, O.W_VH)
+        ref["per_token_loss"] = ref["per_token_loss"] * (mask != 0)
+        out = K.kd_loss_fwd_bwd_multi([torch.from_numpy(f["q_h_t"]).cuda() for f in f8],
+                                      [torch.from_numpy(f["q_W_t"]).cuda() for f in f8], weights,
+                                      G.to_device(h_s, I.BF16), G.to_device(W_s, I.BF16),
+                                      torch.from_numpy(mask).cuda(), tau=base.tau, kind=kind, beta=beta,
+                                      flags=K.FLAG_TEACHER_FP8, teacher_scales=[f["teacher_scale"] for f in f8])
+        torch.cuda.synchronize()
+        G.check(out, ref, f"two fp8 teachers kind={kind}")
