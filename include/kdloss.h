@@ -64,10 +64,11 @@ typedef enum { KD_BF16 = 0, KD_F32 = 1 } kd_dtype;
 /* Storage order of an output head W (mathematical shape [H, V]):
  *   KD_W_HV: W[k * V + v]   (V contiguous)
  *   KD_W_VH: W[v * H + k]   (H contiguous; the order lm_head.weight is kept in)
- * The same order applies to W_t, W_s and grad_W_s.  Both are read and written in place.  KD_W_VH is
- * the faster one (both logit operands contiguous along the contraction; about 5 % ahead) and takes every
- * dtype and size; KD_W_HV takes bf16 inputs with H_t, H_s and V multiples of 64 and no fp8 teacher
- * (KD_ERR_UNSUPPORTED otherwise). */
+ * The same order applies to W_t, W_s and grad_W_s.  KD_W_VH is the faster one (both logit operands
+ * contiguous along the contraction; about 5 % ahead).  KD_W_HV heads are read in place when they are
+ * bf16 with H_t, H_s and V multiples of 64; otherwise they are re-packed into the workspace (which then
+ * holds copies of both heads) by a slow strided pass, a fallback for small problems.  grad_W_s is written
+ * in the caller's order either way.  KD_W_HV with the fp8 teacher returns KD_ERR_UNSUPPORTED. */
 typedef enum { KD_W_HV = 0, KD_W_VH = 1 } kd_wlayout;
 
 /* KD_FLAG_TAU2: multiply the loss, the per-token losses and both gradients by tau^2 (the

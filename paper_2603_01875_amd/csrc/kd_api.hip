@@ -41,12 +41,7 @@ kd_status check_params(const kd_loss_params* p) {
     if (p->in_dtype != KD_BF16) return KD_ERR_UNSUPPORTED;     // the student side stays bf16
     if (p->H_t % 128) return KD_ERR_ALIGN;                     // fp8 k-steps are 128 elements
   }
-  if (p->w_layout == KD_W_HV) {
-    // [H][V] heads are read in place as k-major operands: bf16, whole k-steps, and a vocabulary that
-    // the K-contiguous operand of the grad_h_s product can walk in whole 64-element steps
-    if (p->in_dtype != KD_BF16 || (p->flags & KD_FLAG_TEACHER_FP8)) return KD_ERR_UNSUPPORTED;
-    if (p->H_t % 64 || p->H_s % 64 || p->V % 64) return KD_ERR_UNSUPPORTED;
-  }
+  if (p->w_layout == KD_W_HV && (p->flags & KD_FLAG_TEACHER_FP8)) return KD_ERR_UNSUPPORTED;
   return KD_OK;
 }
 
@@ -71,6 +66,11 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward, si
   q.K_s = (int)round_up(q.in_f32 ? 3 * q.H_s : q.H_s, 64);
   q.prep_Wt = q.in_f32 || q.K_t != q.H_t;
   q.prep_Ws = q.in_f32 || q.K_s != q.H_s;
+  // [H][V] heads are read in place as k-major operands when they are bf16 with whole k-steps and a
+  // vocabulary that the K-contiguous operand of the grad_h_s product can walk in whole 64-element
+  // steps; otherwise both are re-packed (transposing) and the kernels see [V][K] copies
+  q.w_hv_inplace = q.w_hv && !q.prep_Wt && !q.prep_Ws && q.V % 64 == 0;
+  if (q.w_hv && !q.w_hv_inplace) q.prep_Wt = q.prep_Ws = 1;
   // hidden states are also re-packed when a mask is given: valid tokens are compacted to the front
   // (the workspace is sized as if it were, since the size query does not see the mask)
   q.prep_ht = q.prep_hs = 1;
@@ -206,15 +206,15 @@ struct ProfileScope {
 kd_status prepare_operands(const Problem& q, hipStream_t st, bool student, bool teacher) {
   const int* map = q.mask ? q.rowmap : nullptr;     // gather valid tokens to the front
   if (teacher && q.prep_ht && q.t_fp8)     // rows of H_t bytes are gathered as rows of H_t / 2 two-byte words
-    KD_TRY(kd::launch_prepare(q.user_h_t, 0, q.T, q.H_t / 2, const_cast<void*>(q.h_t), q.K_t / 2, 2, map, q.meta, st));
+    KD_TRY(kd::launch_prepare(q.user_h_t, 0, q.T, q.H_t / 2, const_cast<void*>(q.h_t), q.K_t / 2, 2, map, q.meta, 0, st));
   else if (teacher && q.prep_ht)
-    KD_TRY(kd::launch_prepare(q.user_h_t, q.in_f32, q.T, q.H_t, const_cast<void*>(q.h_t), q.K_t, 2, map, q.meta, st));
+    KD_TRY(kd::launch_prepare(q.user_h_t, q.in_f32, q.T, q.H_t, const_cast<void*>(q.h_t), q.K_t, 2, map, q.meta, 0, st));
   if (teacher && q.prep_Wt)
-    KD_TRY(kd::launch_prepare(q.user_W_t, q.in_f32, q.V, q.H_t, const_cast<void*>(q.W_t), q.K_t, 1, nullptr, q.meta, st));
+    KD_TRY(kd::launch_prepare(q.user_W_t, q.in_f32, q.V, q.H_t, const_cast<void*>(q.W_t), q.K_t, 1, nullptr, q.meta, q.w_hv, st));
   if (student && q.prep_hs)
-    KD_TRY(kd::launch_prepare(q.user_h_s, q.in_f32, q.T, q.H_s, const_cast<void*>(q.h_s), q.K_s, 2, map, q.meta, st));
+    KD_TRY(kd::launch_prepare(q.user_h_s, q.in_f32, q.T, q.H_s, const_cast<void*>(q.h_s), q.K_s, 2, map, q.meta, 0, st));
   if (student && q.prep_Ws)
-    KD_TRY(kd::launch_prepare(q.user_W_s, q.in_f32, q.V, q.H_s, const_cast<void*>(q.W_s), q.K_s, 1, nullptr, q.meta, st));
+    KD_TRY(kd::launch_prepare(q.user_W_s, q.in_f32, q.V, q.H_s, const_cast<void*>(q.W_s), q.K_s, 1, nullptr, q.meta, q.w_hv, st));
   return KD_OK;
 }
 
@@ -275,18 +275,21 @@ kd_status run_backward(const Problem* qs, int n_teachers, hipStream_t st) {
       gw.B = q.dz; gw.ldb = q.V_c; gw.N = width;
       gw.k_major = 2; gw.k_rows = q.T_pad;
       gw.out = static_cast<char*>(q.grad_W_s) + (size_t)v0 * q.H_s * gsz; gw.ldo = q.H_s;
-      // grad_h_s[t][h] += sum_v W_s[v][h] dz[t][v]   (the head read vocabulary-major as it lies; dz is
-      // zero from the chunk's last valid column to the end of its 128-column tile)
-      gh.A = static_cast<const char*>(q.W_s) + (size_t)v0 * q.K_s * 2; gh.lda = q.K_s; gh.M = q.H_s;
-      gh.k_major = 1; gh.k_rows = width;
     } else {
-      // heads stored [H][V]: grad_W_s[h][v] = sum_t dz[t][v] h_sT[h][t], dz again read as it lies, now as
-      // the first operand so that the output rows run along the vocabulary
+      // the caller keeps grad_W_s as [H][V]: grad_W_s[h][v] = sum_t dz[t][v] h_sT[h][t], dz again read as it
+      // lies, now as the first operand so that the output rows run along the vocabulary
       gw.A = q.dz; gw.lda = q.V_c; gw.M = width;
       gw.B = q.h_sT; gw.ldb = q.T_pad; gw.N = q.H_s;
       gw.k_major = 1; gw.k_rows = q.T_pad;
       gw.out = static_cast<char*>(q.grad_W_s) + (size_t)v0 * gsz; gw.ldo = q.V;
-      // grad_h_s[t][h] += sum_v W_s[h][v] dz[t][v]: both operands K-contiguous (V % 64 == 0)
+    }
+    if (!q.w_hv_inplace) {
+      // grad_h_s[t][h] += sum_v W_s[v][h] dz[t][v]   (the [V][K] head read vocabulary-major as it lies; dz is
+      // zero from the chunk's last valid column to the end of its 128-column tile)
+      gh.A = static_cast<const char*>(q.W_s) + (size_t)v0 * q.K_s * 2; gh.lda = q.K_s; gh.M = q.H_s;
+      gh.k_major = 1; gh.k_rows = width;
+    } else {
+      // head read in place as [H][V]: grad_h_s[t][h] += sum_v W_s[h][v] dz[t][v], both operands K-contiguous
       gh.A = static_cast<const char*>(q.W_s) + (size_t)v0 * 2; gh.lda = q.V; gh.M = q.H_s;
       gh.k_major = 0; gh.k_rows = width;
     }

@@ -729,8 +729,10 @@ __global__ void transpose_kernel(const bf16_t* src, int64_t ld_src, int R, int C
 // so that sum_k A'[m][k] B'[n][k] = hi.hi + hi.lo + lo.hi.
 // With a row map, destination row j takes source row rowmap[j] for j < n_valid and is zero beyond:
 // the compacted copy of the hidden states.
+// With src_transposed the source is stored [H][R] (a head kept as [H][V]): element (r, c) lies at c * R + r.
+// The strided reads make this the slow way in; it only serves [H][V] heads that must be re-packed anyway.
 __global__ void prepare_kernel(const void* src, int src_f32, int R, int H, bf16_t* dst, int K, int split_mode,
-                               const int* rowmap, const int* meta) {
+                               const int* rowmap, const int* meta, int src_transposed) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (int64_t)R * K) return;
   int r = (int)(i / K);
@@ -741,12 +743,13 @@ __global__ void prepare_kernel(const void* src, int src_f32, int R, int H, bf16_
     live = r < meta[META_N_VALID];
     r = rowmap[r];
   }
+  const int64_t sr = src_transposed ? 1 : H, sc = src_transposed ? R : 1;    // source strides of (r, c)
   if (!live) {
   } else if (!src_f32) {
-    if (c < H) v = ((const bf16_t*)src)[(int64_t)r * H + c];
+    if (c < H) v = ((const bf16_t*)src)[r * sr + c * sc];
   } else if (c < 3 * H) {
     const int part = c / H, col = c - part * H;
-    const float x = ((const float*)src)[(int64_t)r * H + col];
+    const float x = ((const float*)src)[r * sr + col * sc];
     const bf16_t hi = (bf16_t)x;
     const bool want_lo = (split_mode == 1 && part == 2) || (split_mode == 2 && part == 1);
     v = want_lo ? (bf16_t)(x - (float)hi) : hi;
@@ -883,7 +886,7 @@ hipError_t launch_stats(const Problem& p, hipStream_t st) {
   a.partials = p.partials;
   const int grid = p.n_tt * p.n_split;      // worst case; workgroups beyond the device-side plan exit
 #define KD_STATS(K) (p.t_fp8 ? launch_big(stats_kernel<K, true, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
-                     : p.w_hv ? launch_big(stats_kernel<K, false, true>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
+                     : p.w_hv_inplace ? launch_big(stats_kernel<K, false, true>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
                               : launch_big(stats_kernel<K, false, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a))
   switch (p.kind) {
     case 0: return KD_STATS(0);
@@ -899,7 +902,7 @@ hipError_t launch_rows(const Problem& p, hipStream_t st) {
   a.partials = p.partials;
   const int grid = p.n_tt * p.n_split;
 #define KD_ROWS(K) (p.t_fp8 ? launch_big(rows_kernel<K, true, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
-                    : p.w_hv ? launch_big(rows_kernel<K, false, true>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
+                    : p.w_hv_inplace ? launch_big(rows_kernel<K, false, true>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
                              : launch_big(rows_kernel<K, false, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a))
   switch (p.kind) {
     case 2: return KD_ROWS(2);
@@ -944,7 +947,7 @@ hipError_t launch_grad_chunk(const Problem& p, int v0, int width, bool accumulat
   const int tiles = p.n_tt * a.n_vt;
   int grid = tiles < p.n_cu ? tiles : p.n_cu;
 #define KD_GRAD(K) (p.t_fp8 ? launch_big(grad_kernel<K, true, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
-                    : p.w_hv ? launch_big(grad_kernel<K, false, true>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
+                    : p.w_hv_inplace ? launch_big(grad_kernel<K, false, true>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
                              : launch_big(grad_kernel<K, false, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a))
   switch (p.kind) {
     case 0: return KD_GRAD(0);
@@ -989,10 +992,10 @@ hipError_t launch_gemm(const GemmDesc& d, int n_cu, hipStream_t st) {
 }
 
 hipError_t launch_prepare(const void* src, int src_f32, int R, int H, void* dst, int K, int split_mode,
-                          const int* rowmap, const int* meta, hipStream_t st) {
+                          const int* rowmap, const int* meta, int src_transposed, hipStream_t st) {
   const int64_t n = (int64_t)R * K;
   hipLaunchKernelGGL(prepare_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, src, src_f32, R, H,
-                     (bf16_t*)dst, K, split_mode, rowmap, meta);
+                     (bf16_t*)dst, K, split_mode, rowmap, meta, src_transposed);
   return hipGetLastError();
 }
 

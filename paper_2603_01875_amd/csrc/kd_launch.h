@@ -26,7 +26,9 @@ struct Problem {
   const void *h_t, *W_t, *h_s, *W_s;                   // bf16 [rows][K_t or K_s] as the kernels read them
   const void *user_h_t, *user_W_t, *user_h_s, *user_W_s;  // the caller's arrays
   int in_f32;                   // inputs are fp32
-  int w_hv;                     // heads (and grad_W_s) are stored [H][V]
+  int w_hv;                     // the caller's heads and grad_W_s are stored [H][V]
+  int w_hv_inplace;             // ... and the kernels read the heads in that order, in place (else they are
+                                // re-packed into [V][K] copies like any operand that needs re-packing)
   int t_fp8;                    // teacher operands are e4m3 bytes (K_t = H_t elements = bytes per row)
   float t_scale;                // ... and z_t = t_scale * (product of the codes)
   int prep_ht, prep_Wt, prep_hs, prep_Ws;   // which operands are re-packed into the workspace
@@ -83,6 +85,6 @@ hipError_t launch_gemm(const GemmDesc& d, int n_cu, hipStream_t st);
 hipError_t launch_gradh_finish(const Problem& p, hipStream_t st);
 // dst bf16 [R][K]: mode 0 = copy, 1 = fp32 split as [hi|hi|lo], 2 = fp32 split as [hi|lo|hi]; zero-padded to K
 hipError_t launch_prepare(const void* src, int src_f32, int R, int H, void* dst, int K, int split_mode,
-                          const int* rowmap, const int* meta, hipStream_t st);
+                          const int* rowmap, const int* meta, int src_transposed, hipStream_t st);
 
 }  // namespace kd

@@ -300,3 +300,28 @@ def test_low_temperature_near_one_hot(kind, beta, tau):
     s = 1.0 / (data["mask"].sum() * tau)
     noise = dict(grad_h_s=1e-4 * s * np.abs(data["W_s"]).max(), grad_W_s=1e-4 * s * np.abs(data["h_s"]).max())
     G.check(G.run_gpu(cfg, data), G.run_oracle(cfg, data), f"kind={kind} tau={tau}", noise)
+
+
+@pytest.mark.parametrize("dtype,H_t,H_s,V", [(I.BF16, 200, 72, 1000), (I.BF16, 128, 64, 1000), (I.F32, 96, 64, 1544),
+                                             (I.F32, 128, 128, 1024)])
+def test_hidden_major_heads_off_the_fast_path(dtype, H_t, H_s, V, monkeypatch):
+    """[H,V] heads that cannot be read in place (fp32, or sizes off the 64-element grid) go through the
+    transposing re-pack; grad_W_s still comes back as [H_s, V]."""
+    import torch
+    from oracle import kd_oracle as O
+    from paper_2603_01875_amd import kdloss as K
+    monkeypatch.setenv("KD_VOCAB_CHUNK", "512")
+    cfg = I.scaled(I.workload("tiny_fkl_f32" if dtype == I.F32 else "rkl_bf16"), batch=2, seq=150, H_t=H_t, H_s=H_s,
+                   V=V, mask="tail25")
+    data = I.generate(cfg)
+    hv = {k: np.ascontiguousarray(data[k].T) for k in ("W_t", "W_s")}
+    ref = O.kd_loss_fwd_bwd(data["h_t"], hv["W_t"], data["h_s"], hv["W_s"], data["mask"], cfg.tau, cfg.kind, cfg.beta,
+                            O.W_HV)
+    ref["per_token_loss"] = ref["per_token_loss"] * (data["mask"] != 0)
+    dev = lambda x: G.to_device(x, dtype)
+    out = K.kd_loss_fwd_bwd(dev(data["h_t"]), dev(hv["W_t"]), dev(data["h_s"]), dev(hv["W_s"]),
+                            torch.from_numpy(data["mask"]).cuda(), tau=cfg.tau, kind=cfg.kind, beta=cfg.beta,
+                            w_layout=K.W_HV)
+    torch.cuda.synchronize()
+    assert tuple(out["grad_W_s"].shape) == (H_s, V)
+    G.check(out, ref, f"[H,V] heads dtype={dtype} H_t={H_t} H_s={H_s} V={V}")
