@@ -757,6 +757,18 @@ __global__ void prepare_kernel(const void* src, int src_f32, int R, int H, bf16_
   dst[i] = v;
 }
 
+// The common case of the above, 16 bytes per thread: bf16 (or byte) rows that only have to be gathered
+// (K == H, H a multiple of 8).  Row j of dst is row rowmap[j] of src for j < n_valid, zero beyond.
+__global__ void gather_rows_kernel(const u32x4* src, u32x4* dst, int R, int chunks_per_row, const int* rowmap,
+                                   const int* meta) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)R * chunks_per_row) return;
+  const int j = (int)(i / chunks_per_row), c = (int)(i % chunks_per_row);
+  u32x4 v = {0u, 0u, 0u, 0u};
+  if (j < meta[META_N_VALID]) v = src[(int64_t)rowmap[j] * chunks_per_row + c];
+  dst[i] = v;
+}
+
 // Measurement aid: what the matrix pipe sustains with nothing else going on.  Same occupancy as the
 // logit kernels (one workgroup of 8 waves per CU, forced by the LDS request), 8 independent 32x32x16
 // accumulators per wave, operands taken from the caller's buffer (the shader clock under MFMA load
@@ -994,6 +1006,12 @@ hipError_t launch_gemm(const GemmDesc& d, int n_cu, hipStream_t st) {
 hipError_t launch_prepare(const void* src, int src_f32, int R, int H, void* dst, int K, int split_mode,
                           const int* rowmap, const int* meta, int src_transposed, hipStream_t st) {
   const int64_t n = (int64_t)R * K;
+  if (!src_f32 && !src_transposed && K == H && H % 8 == 0 && rowmap) {
+    const int64_t chunks = n / 8;
+    hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st,
+                       (const u32x4*)src, (u32x4*)dst, R, H / 8, rowmap, meta);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(prepare_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, src, src_f32, R, H,
                      (bf16_t*)dst, K, split_mode, rowmap, meta, src_transposed);
   return hipGetLastError();
