@@ -46,3 +46,32 @@ def test_captured_call_replays_bit_exactly(kind, beta, monkeypatch):
         torch.cuda.synchronize()
         for k in ref:
             assert torch.equal(outs[1][k], ref[k]), f"replay {rep}: {k}"
+
+
+def test_two_calls_on_two_streams_do_not_interfere():
+    """The library keeps no state between calls: two problems enqueued on two streams (default
+    priority), each with its own workspace, give the results they give one after the other."""
+    import torch
+    from paper_2603_01875_amd import kdloss as K
+    cfgs = [I.scaled(I.workload("fkl_bf16"), batch=2, seq=300, H_t=256, H_s=128, V=8200),
+            I.scaled(I.workload("jsd_bf16"), batch=1, seq=500, H_t=192, H_s=64, V=6152)]
+    probs = []
+    for cfg in cfgs:
+        data = I.generate(cfg)
+        d = {k: G.to_device(data[k], cfg.dtype) for k in ("h_t", "W_t", "h_s", "W_s")}
+        d["mask"] = torch.from_numpy(data["mask"]).cuda()
+        probs.append((cfg, d))
+    seq = [K.kd_loss_fwd_bwd(d["h_t"], d["W_t"], d["h_s"], d["W_s"], d["mask"], tau=c.tau, kind=c.kind, beta=c.beta)
+           for c, d in probs]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    conc = [None, None]
+    for rep in range(3):
+        for i, (c, d) in enumerate(probs):
+            with torch.cuda.stream(streams[i]):
+                conc[i] = K.kd_loss_fwd_bwd(d["h_t"], d["W_t"], d["h_s"], d["W_s"], d["mask"], tau=c.tau, kind=c.kind,
+                                            beta=c.beta)
+        torch.cuda.synchronize()
+        for a, b in zip(seq, conc):
+            for k in ("loss", "per_token_loss", "grad_h_s", "grad_W_s"):
+                assert torch.equal(a[k], b[k]), k
