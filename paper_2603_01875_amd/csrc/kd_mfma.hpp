@@ -181,8 +181,18 @@ __device__ __forceinline__ void km_read(KmFrag& f, uint32_t addr) {
 }
 template <int N>
 __device__ __forceinline__ void km_wait(KmFrag (&f)[N]) {
-#pragma unroll
-  for (int i = 0; i < N; ++i) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[i].lo), "+v"(f[i].hi));
+  static_assert(N >= 1 && N <= 4, "fragments per wave and operand");
+  if constexpr (N == 1)
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0].lo), "+v"(f[0].hi));
+  else if constexpr (N == 2)
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0].lo), "+v"(f[0].hi), "+v"(f[1].lo), "+v"(f[1].hi));
+  else if constexpr (N == 3)
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(f[0].lo), "+v"(f[0].hi), "+v"(f[1].lo), "+v"(f[1].hi), "+v"(f[2].lo), "+v"(f[2].hi));
+  else
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(f[0].lo), "+v"(f[0].hi), "+v"(f[1].lo), "+v"(f[1].hi), "+v"(f[2].lo), "+v"(f[2].hi),
+                   "+v"(f[3].lo), "+v"(f[3].hi));
 }
 template <int N>
 __device__ __forceinline__ void km_wait(bf16x8 (&)[N]) {}
