@@ -287,24 +287,31 @@ struct RowTerm {
       return 0.5f * sg;
     }
     const float wt = (KIND == 5) ? 1.f - w : w;          // weight of p_t in the mixture
-    const float M = fmaf(wt, pt, (1.f - wt) * ps);
-    // The hardware logarithm takes subnormal arguments for zero (-inf, and inf * 0 further on): a
-    // mixture below the smallest normal number counts as absent, like an exact zero (p_t = p_s = 0);
-    // what it would contribute is below 1e-36.
-    const bool live = M >= 1.17549435e-38f;
-    const float lm = live ? flog2(M) : 0.f;
+    // log M is taken relative to the larger of the two probabilities: with d = ls - lt and q = 2^-|d| <= 1,
+    //   p_t >= p_s:  M / p_t = wt + (1-wt) q      p_t < p_s:  M / p_s = wt q + (1-wt)
+    // so the logarithm's argument lies in [min(wt, 1-wt), 1]: no large logarithms are subtracted from one
+    // another (the hardware log of M itself, of size log2 V, is half an ulp short on average, which
+    // showed as a bias of 3e-7 in small losses), and nothing degenerates where p_t and p_s underflow.
+    const float d = ls - lt;
+    const bool t_big = d <= 0.f;
+    const float q = fexp2(t_big ? d : -d);
+    const float mix = t_big ? fmaf(1.f - wt, q, wt) : fmaf(wt, q, 1.f - wt);
+    const float lmix = flog2(mix);
+    const float lt_lm = t_big ? -lmix : -d - lmix;       // lt - lm
+    const float ls_lm = t_big ? d - lmix : -lmix;        // ls - lm
+    const float inv = __builtin_amdgcn_rcpf(mix);
     if (KIND == 2) {
-      if (ACC) { a1 = fmaf(pt, lt - lm, a1); a2 = fmaf(ps, ls - lm, a2); }
-      return (1.f - w) * LN2 * (ls - lm);
+      if (ACC) { a1 = fmaf(pt, lt_lm, a1); a2 = fmaf(ps, ls_lm, a2); }
+      return (1.f - w) * LN2 * ls_lm;
     }
     if (KIND == 4) {
-      const float r = live ? fexp2(lt - lm) : 0.f;       // p_t / M
-      if (ACC) { a1 = fmaf(pt, lt - lm, a1); a2 = fmaf(ps, r, a2); }
+      const float r = t_big ? inv : q * inv;             // p_t / M
+      if (ACC) { a1 = fmaf(pt, lt_lm, a1); a2 = fmaf(ps, r, a2); }
       return -(1.f - w) * r;
     }
-    const float r = live ? fexp2(ls - lm) : 0.f;         // p_s / M
-    const float cc = fmaf(LN2, ls - lm, 1.f - w * r);
-    if (ACC) { a1 = fmaf(ps, ls - lm, a1); a2 = fmaf(ps, cc, a2); }
+    const float r = t_big ? q * inv : inv;               // p_s / M
+    const float cc = fmaf(LN2, ls_lm, 1.f - w * r);
+    if (ACC) { a1 = fmaf(ps, ls_lm, a1); a2 = fmaf(ps, cc, a2); }
     return cc;
   }
 };
@@ -642,11 +649,14 @@ __global__ void combine_kernel(const float* partials, const int* meta, int T_pad
     Ss = fmaf(q[3 * T_pad], ws, Ss);
     X = fmaf(q[4 * T_pad], kind == 0 ? wt : ws, X);
   }
-  const float Lt = Mt + flog2(St), Ls = Ms + flog2(Ss);
-  float loss = 0.f;
-  if (kind == 0) loss = LN2 * (c * X / St - Lt + Ls);   // kinds >= 2: filled in by combine_rows_kernel
-  if (kind == 1) loss = LN2 * (c * X / Ss - Ls + Lt);
-  rowinfo[t] = f32x4{Lt, Ls, 0.f, loss};
+  // The row loss is a difference of quantities of size log2 V, far larger than itself when the two
+  // distributions are close: this last step is done in double (one thread per token, so it costs nothing).
+  const double Ltd = (double)Mt + log2((double)St), Lsd = (double)Ms + log2((double)Ss);
+  double lossd = 0.0;
+  if (kind == 0) lossd = (double)c * X / St - Ltd + Lsd;   // kinds >= 2: filled in by combine_rows_kernel
+  if (kind == 1) lossd = (double)c * X / Ss - Lsd + Ltd;
+  const float loss = (float)(0.6931471805599453 * lossd);
+  rowinfo[t] = f32x4{(float)Ltd, (float)Lsd, 0.f, loss};
   row_loss[t] = loss;
 }
 

@@ -78,7 +78,8 @@ def check(out, ref, what="", extra_tol=None):
     assert rel <= LOSS_RTOL, f"{what}: loss {loss} vs {ref['loss']} (rel {rel:.2e})"
     ptl = to_host(out["per_token_loss"])
     scale = max(np.abs(ref["per_token_loss"]).max(), 1e-30)
-    assert np.abs(ptl - ref["per_token_loss"]).max() <= 2e-3 * scale, f"{what}: per-token loss"
+    # a row loss is summed in fp32 over V terms: below about 1e-4 its absolute resolution (a few 1e-7) shows
+    assert np.abs(ptl - ref["per_token_loss"]).max() <= 2e-3 * scale + 5e-7, f"{what}: per-token loss"
     for name in ("grad_h_s", "grad_W_s"):
         g = to_host(out[name])
         assert np.isfinite(g).all(), f"{what}: {name} not finite"

@@ -11,6 +11,12 @@ from tests import gpu_util as G
 
 pytestmark = pytest.mark.gpu
 
+# The fp8 MFMA sums its 64 products per instruction with about 14 bits below the largest one (measured
+# 6e-5 relative on a single 32x32x64 block), so fp8 teacher logits deviate by up to 1e-4 relative from the
+# exact sum of the same products: far below the quantisation step (2^-4) and the tolerances, but it widens
+# the band in which TVD's sign(p_s - p_t) may come out either way.
+FP8_TIE_GAP = 3e-4
+
 
 @pytest.fixture(autouse=True)
 def _chunk_env(monkeypatch):
@@ -78,7 +84,7 @@ def test_fp8_teacher_other_divergences(kind, beta):
     data = I.generate(cfg)
     f8 = G.fp8_teacher(data)
     d = dict(data); d["h_t"], d["W_t"] = f8["h_t"], f8["W_t"]
-    extra = G.tvd_tie_allowance(cfg, d) if kind == I.TVD else None
+    extra = G.tvd_tie_allowance(cfg, d, rel_gap=FP8_TIE_GAP) if kind == I.TVD else None
     G.check(_run_fp8(cfg, data, f8), _oracle_fp8(cfg, data, f8), f"kind {kind} fp8 teacher", extra)
 
 

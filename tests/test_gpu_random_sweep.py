@@ -83,7 +83,8 @@ def test_random_case_other_layout_or_fp8_teacher(seed, monkeypatch):
                                 dev(data["h_s"]), dev(data["W_s"]), mask, tau=cfg.tau, kind=cfg.kind, beta=cfg.beta,
                                 flags=K.FLAG_TEACHER_FP8, teacher_scale=f8["teacher_scale"])
     torch.cuda.synchronize()
-    extra = G.tvd_tie_allowance(cfg, d) if cfg.kind == I.TVD else None
+    # fp8 MFMA: about 14 bits below the largest product inside one instruction (see test_gpu_fp8.py)
+    extra = G.tvd_tie_allowance(cfg, d, rel_gap=3e-4 if mode == "fp8" else 2e-5) if cfg.kind == I.TVD else None
     if extra is not None and mode == "hv":
         extra = dict(grad_h_s=extra["grad_h_s"], grad_W_s=extra["grad_W_s"].T)
     G.check(out, ref, what, extra)
