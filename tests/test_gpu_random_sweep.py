@@ -88,3 +88,81 @@ def test_random_case_other_layout_or_fp8_teacher(seed, monkeypatch):
     if extra is not None and mode == "hv":
         extra = dict(grad_h_s=extra["grad_h_s"], grad_W_s=extra["grad_W_s"].T)
     G.check(out, ref, what, extra)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_feature_combination(seed, monkeypatch):
+    """Random combinations of the library's options: fp8 teacher, [H,V] heads, fp32 inputs or gradients, one
+    to three teachers, temperatures from 0.05 to 20, sparse masks, chunk sizes.  Two documented fp32 limits
+    are allowed for: losses below 1e-4 are skipped, and where a divergence saturates (low temperatures) dz
+    may carry noise of 2e-5 of its natural scale 1 / (n tau)."""
+    import torch
+    from oracle import kd_oracle as O
+    from paper_2603_01875_amd import kdloss as K
+    rng = np.random.default_rng(90000 + seed)
+    kind = int(rng.integers(0, 6))
+    fp8 = bool(rng.integers(0, 3) == 0)
+    hv = (not fp8) and bool(rng.integers(0, 3) == 0)
+    f32 = (not fp8) and bool(rng.integers(0, 6) == 0)
+    nteach = 1 if (hv or f32) else int(rng.choice([1, 1, 2, 3]))
+    H_s, V = 8 * int(rng.integers(1, 96)), 8 * int(rng.integers(1, 2500))
+    T_b, T_s = int(rng.integers(1, 5)), int(rng.integers(1, 400))
+    tau = float(np.exp(rng.uniform(np.log(0.05), np.log(20.0))))
+    beta = float(rng.uniform(0.02, 0.98))
+    base = I.KDConfig(name=f"s{seed}", batch=T_b, seq=T_s, H_t=64, H_s=H_s, V=V, dtype=I.F32 if f32 else I.BF16,
+                      w_t_std=0.02, w_s_std=float(rng.choice([0.02, 0.06, 0.2])), rms_norm=bool(rng.integers(0, 2)),
+                      kind=kind, tau=tau, beta=beta, mask=str(rng.choice(["ones", "tail25", "bernoulli10"])),
+                      seed=123000 + seed)
+    monkeypatch.setenv("KD_VOCAB_CHUNK", str(int(rng.choice([256, 1024, 4096, 0]))))
+    ds = []
+    for k in range(nteach):
+        H_t = (128 if fp8 else 8) * int(rng.integers(1, 9 if fp8 else 96))
+        ds.append(I.generate(I.scaled(base, H_t=H_t, w_t_std=float(rng.choice([0.02, 0.05, 0.2, 0.5])),
+                                      seed=base.seed + 7 * k)))
+    data = ds[0]
+    if rng.integers(0, 5) == 0:
+        data["mask"] = (rng.random(base.T) < 0.1).astype(np.uint8)
+    mask = data["mask"]
+    weights = [float(x) for x in rng.uniform(0.1, 1.0, nteach)]
+    gdt = K.F32 if (f32 or rng.integers(0, 3) == 0) else K.BF16
+    what = (f"seed={seed} kind={kind} fp8={fp8} hv={hv} f32={f32} teachers={nteach} T={base.T} H_s={H_s} V={V} "
+            f"tau={tau:.3f} beta={beta:.2f} mask={base.mask}")
+    dev = lambda x: G.to_device(x, I.F32 if f32 else I.BF16)
+    tm = torch.from_numpy(mask).cuda()
+    teach = []                       # (h_t, W_t as the oracle sees them, device h_t, device W_t, scale)
+    for d in ds:
+        if fp8:
+            f8 = G.fp8_teacher(d)
+            teach.append((f8["h_t"], f8["W_t"], torch.from_numpy(f8["q_h_t"]).cuda(),
+                          torch.from_numpy(f8["q_W_t"]).cuda(), f8["teacher_scale"]))
+        else:
+            teach.append((d["h_t"], d["W_t"], dev(d["h_t"]),
+                          dev(np.ascontiguousarray(d["W_t"].T) if hv else d["W_t"]), 0.0))
+    Ws_o = np.ascontiguousarray(data["W_s"].T) if hv else data["W_s"]
+    flags = K.FLAG_TEACHER_FP8 if fp8 else 0
+    if nteach == 1:
+        ref = O.kd_loss_fwd_bwd(teach[0][0], np.ascontiguousarray(teach[0][1].T) if hv else teach[0][1], data["h_s"],
+                                Ws_o, mask, tau, kind, beta, O.W_HV if hv else O.W_VH)
+        out = K.kd_loss_fwd_bwd(teach[0][2], teach[0][3], dev(data["h_s"]), dev(Ws_o), tm, tau=tau, kind=kind,
+                                beta=beta, w_layout=K.W_HV if hv else K.W_VH, grad_dtype=gdt, flags=flags,
+                                teacher_scale=teach[0][4])
+    else:
+        ref = O.kd_loss_multi([t[0] for t in teach], [t[1] for t in teach], weights, data["h_s"], data["W_s"], mask,
+                              tau, kind, beta, O.W_VH)
+        out = K.kd_loss_fwd_bwd_multi([t[2] for t in teach], [t[3] for t in teach], weights, dev(data["h_s"]),
+                                      dev(data["W_s"]), tm, tau=tau, kind=kind, beta=beta, grad_dtype=gdt, flags=flags,
+                                      teacher_scales=[t[4] for t in teach] if fp8 else None)
+    torch.cuda.synchronize()
+    ref["per_token_loss"] = ref["per_token_loss"] * (mask != 0)
+    if ref["loss"] < 1e-4 and kind != I.TVD:
+        pytest.skip("loss below the fp32 resolution of the row sums")
+    sc = (sum(weights) if nteach > 1 else 1.0) / (max(mask.sum(), 1) * tau)
+    allow = dict(grad_h_s=2e-5 * sc * np.abs(data["W_s"]).max() * np.sqrt(V),
+                 grad_W_s=2e-5 * sc * np.abs(data["h_s"]).max() * np.sqrt(base.T))
+    if kind == I.TVD:
+        for w, t in zip(weights if nteach > 1 else [1.0], teach):
+            dd = dict(data); dd["h_t"], dd["W_t"] = t[0], t[1]
+            e = G.tvd_tie_allowance(I.scaled(base, H_t=t[0].shape[1]), dd, rel_gap=3e-4 if fp8 else 2e-5)
+            allow["grad_h_s"] = allow["grad_h_s"] + w * e["grad_h_s"]
+            allow["grad_W_s"] = allow["grad_W_s"] + w * (e["grad_W_s"].T if hv else e["grad_W_s"])
+    G.check(out, ref, what, allow)
