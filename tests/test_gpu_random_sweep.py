@@ -143,9 +143,14 @@ def test_random_feature_combination(seed, monkeypatch):
     if nteach == 1:
         ref = O.kd_loss_fwd_bwd(teach[0][0], np.ascontiguousarray(teach[0][1].T) if hv else teach[0][1], data["h_s"],
                                 Ws_o, mask, tau, kind, beta, O.W_HV if hv else O.W_VH)
+        acc0 = None
+        if rng.integers(0, 3) == 0:          # gradient accumulation onto what an earlier micro-batch left
+            a0 = (rng.standard_normal(Ws_o.shape) * max(np.abs(ref["grad_W_s"]).max(), 1e-12)).astype(np.float32)
+            acc0 = torch.from_numpy(a0).cuda().to(torch.float32 if gdt == K.F32 else torch.bfloat16)
+            ref["grad_W_s"] = ref["grad_W_s"] + G.to_host(acc0)
         out = K.kd_loss_fwd_bwd(teach[0][2], teach[0][3], dev(data["h_s"]), dev(Ws_o), tm, tau=tau, kind=kind,
                                 beta=beta, w_layout=K.W_HV if hv else K.W_VH, grad_dtype=gdt, flags=flags,
-                                teacher_scale=teach[0][4])
+                                teacher_scale=teach[0][4], grad_W_s=acc0, accumulate_grad_W=acc0 is not None)
     else:
         ref = O.kd_loss_multi([t[0] for t in teach], [t[1] for t in teach], weights, data["h_s"], data["W_s"], mask,
                               tau, kind, beta, O.W_VH)
