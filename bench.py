@@ -109,6 +109,7 @@ def main():
 
     # timed region: exactly `steps` steps, bracketed by synchronisation; the dominant kernel
     # (logit tiles + online log-sum-exp, one launch per step) is bracketed by events inside it
+    clk = K.ShaderClock().__enter__()      # shader clock seen by workgroup 0 of the last statistics kernel
     kt = K.KernelTimer(K.PROF_STATS, args.steps)
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
@@ -138,8 +139,12 @@ def main():
             torch.cuda.synchronize()
         fam[name] = sum(t.durations_ms())
 
+    torch.cuda.synchronize()
+    stats_ghz = clk.ghz()
     # the matrix pipe's own ceiling on this machine, measured right after the timed region (a few ms)
     probe = K.probe_mfma_rate()
+    probe_ghz = clk.ghz()
+    clk.__exit__()
 
     n_valid = int(data["mask"].sum())
     # masked tokens are compacted away on the device: the kernels work on the valid tokens, rounded up
@@ -173,7 +178,12 @@ def main():
                      "peak": peak, "unit": "TFLOP/s", "frac": stats_tflops / peak,
                      "traffic": traffic, "launch_ms": stats_avg, "flop_per_launch": logit_flop,
                      "mfma_only_probe_tflops": probe,
-                     "frac_of_probe": None if args.teacher_fp8 else stats_tflops / probe},
+                     "frac_of_probe": None if args.teacher_fp8 else stats_tflops / probe,
+                     # the shader clock each of the two kernels ran at (cycles / 100 MHz ticks inside the kernel)
+                     # and the share of the bf16 MFMA rate at THAT clock (256 CUs x 4 SIMDs x 1024 flop/clk)
+                     "shader_clock_ghz": stats_ghz, "probe_shader_clock_ghz": probe_ghz,
+                     "frac_at_shader_clock": None if args.teacher_fp8 else
+                     stats_tflops / (1024 * 1024 * stats_ghz * 1e9 / 1e12)},
         "tflops_algorithmic": flop_alg / (ms_per_step * 1e-3) / 1e12,
         "tflops_executed": flop_exec / (ms_per_step * 1e-3) / 1e12,
         "mfma_frac_whole_step": (flop_exec / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS if not args.teacher_fp8 else

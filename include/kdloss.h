@@ -211,6 +211,13 @@ int kd_loss_profile_count(void);
  * bf16 values; the shader clock under this load depends on them, so pass values like real data).
  * Executes KD_PROBE_FLOP_PER_ITER * iters flop.  `sink` (device, 256 * 512 floats) receives sums that
  * only keep the work alive.  Time the launch with events on `hip_stream`. */
+/* Benchmark aid: while set (per host thread; NULL clears it), workgroup 0 of the statistics kernel of
+ * kd_loss_fwd / kd_loss_fwd_bwd and of kd_probe_mfma_rate stores into the two int64 at this device
+ * address the shader-clock cycles and the 100 MHz reference ticks that its main loop took: their ratio
+ * is the shader clock the GPU held under that kernel's load (it is set by the power limit, far below the
+ * nominal 2.4 GHz for these kernels).  Host only. */
+kd_status kd_loss_profile_clock(void* two_int64_device);
+
 #define KD_PROBE_FLOP_PER_ITER (256.0 * 8 * 8 * 2 * 32 * 32 * 16)
 kd_status kd_probe_mfma_rate(const void* operands, int iters, float* sink, void* hip_stream);
 

@@ -179,6 +179,7 @@ struct ProfileHook {
   int used = 0;     // pairs recorded
 };
 thread_local ProfileHook g_hook;
+thread_local long long* g_clock_out = nullptr;   // kd_loss_profile_clock
 
 struct ProfileScope {
   bool on;
@@ -322,6 +323,7 @@ kd_status check_buffers(const kd_loss_params* params, const void* h_t, const voi
   plan(params, q, L, backward, teacher_base);
   if (workspace_bytes < L.total) return KD_ERR_WORKSPACE;
   q.h_t = h_t; q.W_t = W_t; q.h_s = h_s; q.W_s = W_s; q.mask = mask;
+  q.clock_out = g_clock_out;
   q.loss = loss;
   q.grad_h_s = grad_h_s; q.grad_W_s = grad_W_s;
   carve(q, L, workspace);
@@ -459,7 +461,13 @@ kd_status kd_probe_mfma_rate(const void* operands, int iters, float* sink, void*
   if (!operands || !sink) return KD_ERR_NULL;
   if (iters < 1 || iters > (1 << 24)) return KD_ERR_PARAM;
   if (!aligned16(operands) || !aligned16(sink)) return KD_ERR_ALIGN;
-  KD_TRY(kd::launch_mfma_probe(operands, iters, sink, kd::kNumCU, static_cast<hipStream_t>(hip_stream)));
+  KD_TRY(kd::launch_mfma_probe(operands, iters, sink, g_clock_out, kd::kNumCU, static_cast<hipStream_t>(hip_stream)));
+  return KD_OK;
+}
+
+kd_status kd_loss_profile_clock(void* two_int64_device) {
+  if (reinterpret_cast<uintptr_t>(two_int64_device) & 7u) return KD_ERR_ALIGN;
+  g_clock_out = static_cast<long long*>(two_int64_device);
   return KD_OK;
 }
 

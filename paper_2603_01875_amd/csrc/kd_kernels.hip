@@ -81,6 +81,8 @@ struct LogitArgs {
   bf16_t* dz;          // [T_pad][ldz]   chunk of dL/dz_s, vocabulary contiguous
   int ldz;
   int dz_accumulate;   // add to dz instead of overwriting it (further teachers of a multi-teacher call)
+  long long* clock_out;// measurement aid (may be null): workgroup 0 of the statistics kernel stores the shader
+                       // cycles and the 100 MHz ticks its tile loop took
 };
 
 // TF8: the teacher operands are e4m3 bytes (one byte per element, 128 elements per k-step).
@@ -433,7 +435,12 @@ KD_LOGIT_KERNEL void stats_kernel(const LogitArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   SplitWork<TF8, WHV> work(a);
   StatsEpi<KIND> epi(a.c, a.t_scale);
+  const long long c0 = clock64(), r0 = wall_clock64();
   tile_loop<2, LCfg, WHV ? 1 : 0, TF8>(work, epi, WHV ? a.V : a.H_s, WHV ? a.V : a.H_t, a.H_s, a.H_t, smem);
+  if (a.clock_out && blockIdx.x == 0 && threadIdx.x == 0) {
+    a.clock_out[0] = clock64() - c0;
+    a.clock_out[1] = wall_clock64() - r0;
+  }
   if (work.cnt > 0) epi.write(a, work.tt, work.split);
 }
 
@@ -783,7 +790,9 @@ __global__ void gather_rows_kernel(const u32x4* src, u32x4* dst, int R, int chun
 // logit kernels (one workgroup of 8 waves per CU, forced by the LDS request), 8 independent 32x32x16
 // accumulators per wave, operands taken from the caller's buffer (the shader clock under MFMA load
 // depends on the operand values, so they should look like real data).
-__global__ __launch_bounds__(512) void mfma_probe_kernel(const bf16x8* operands, int iters, float* sink) {
+__global__ __launch_bounds__(512) void mfma_probe_kernel(const bf16x8* operands, int iters, float* sink,
+                                                         long long* clock_out) {
+  const long long c0 = clock64(), r0 = wall_clock64();
   const int lane_id = (blockIdx.x * 512 + threadIdx.x) & 2047;      // 2048 x 4 x 16 B = 128 KiB of operands
   bf16x8 a0 = operands[lane_id * 4 + 0], a1 = operands[lane_id * 4 + 1];
   bf16x8 b0 = operands[lane_id * 4 + 2], b1 = operands[lane_id * 4 + 3];
@@ -808,6 +817,10 @@ __global__ __launch_bounds__(512) void mfma_probe_kernel(const bf16x8* operands,
 #pragma unroll
     for (int r = 0; r < 16; ++r) s += c[i][r];
   sink[blockIdx.x * 512 + threadIdx.x] = s;
+  if (clock_out && blockIdx.x == 0 && threadIdx.x == 0) {
+    clock_out[0] = clock64() - c0;
+    clock_out[1] = wall_clock64() - r0;
+  }
 }
 
 // OCP e4m3 (4 exponent bits, bias 7, 3 mantissa bits, no infinities, 0x7f = NaN, largest 448):
@@ -906,6 +919,7 @@ hipError_t launch_stats(const Problem& p, hipStream_t st) {
   LogitArgs a = make_logit_args(p);
   a.vt0 = 0; a.n_vt = p.n_vt;
   a.partials = p.partials;
+  a.clock_out = p.clock_out;
   const int grid = p.n_tt * p.n_split;      // worst case; workgroups beyond the device-side plan exit
 #define KD_STATS(K) (p.t_fp8 ? launch_big(stats_kernel<K, true, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
                      : p.w_hv_inplace ? launch_big(stats_kernel<K, false, true>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
@@ -1027,12 +1041,13 @@ hipError_t launch_prepare(const void* src, int src_f32, int R, int H, void* dst,
   return hipGetLastError();
 }
 
-hipError_t launch_mfma_probe(const void* operands, int iters, float* sink, int n_cu, hipStream_t st) {
-  struct { const bf16x8* o; int it; float* s; } a{(const bf16x8*)operands, iters, sink};
+hipError_t launch_mfma_probe(const void* operands, int iters, float* sink, long long* clock_out, int n_cu,
+                             hipStream_t st) {
+  struct { const bf16x8* o; int it; float* s; long long* c; } a{(const bf16x8*)operands, iters, sink, clock_out};
   hipError_t e = hipFuncSetAttribute((const void*)mfma_probe_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                      LCfg::SMEM_BYTES);
   if (e != hipSuccess) return e;
-  void* params[] = {&a.o, &a.it, &a.s};
+  void* params[] = {&a.o, &a.it, &a.s, &a.c};
   return hipLaunchKernel((const void*)mfma_probe_kernel, dim3(n_cu), dim3(512), params, LCfg::SMEM_BYTES, st);
 }
 

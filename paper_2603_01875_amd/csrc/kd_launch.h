@@ -29,6 +29,7 @@ struct Problem {
   int w_hv;                     // the caller's heads and grad_W_s are stored [H][V]
   int w_hv_inplace;             // ... and the kernels read the heads in that order, in place (else they are
                                 // re-packed into [V][K] copies like any operand that needs re-packing)
+  long long* clock_out;         // measurement aid, see kd_loss_profile_clock (null unless set)
   int t_fp8;                    // teacher operands are e4m3 bytes (K_t = H_t elements = bytes per row)
   float t_scale;                // ... and z_t = t_scale * (product of the codes)
   int prep_ht, prep_Wt, prep_hs, prep_Ws;   // which operands are re-packed into the workspace
@@ -71,7 +72,8 @@ struct GemmDesc {
 };
 
 hipError_t launch_rowmap(const Problem& p, hipStream_t st);
-hipError_t launch_mfma_probe(const void* operands, int iters, float* sink, int n_cu, hipStream_t st);
+hipError_t launch_mfma_probe(const void* operands, int iters, float* sink, long long* clock_out, int n_cu,
+                             hipStream_t st);
 hipError_t launch_quantize_e4m3(const void* src, int src_f32, int64_t n, float inv_scale, void* dst, hipStream_t st);
 hipError_t launch_stats(const Problem& p, hipStream_t st);
 hipError_t launch_combine(const Problem& p, hipStream_t st);

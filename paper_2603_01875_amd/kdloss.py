@@ -66,6 +66,8 @@ def lib():
         L.kd_loss_fwd_bwd_multi.restype = ctypes.c_int
         L.kd_quantize_e4m3.argtypes = [vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, vp, vp]
         L.kd_quantize_e4m3.restype = ctypes.c_int
+        L.kd_loss_profile_clock.argtypes = [vp]
+        L.kd_loss_profile_clock.restype = ctypes.c_int
         L.kd_probe_mfma_rate.argtypes = [vp, ctypes.c_int, vp, vp]
         L.kd_probe_mfma_rate.restype = ctypes.c_int
         L.kd_loss_profile_hook.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_void_p), ctypes.c_int]
@@ -152,6 +154,26 @@ class KernelTimer:
 
 
 PROBE_FLOP_PER_ITER = 256.0 * 8 * 8 * 2 * 32 * 32 * 16
+
+
+class ShaderClock:
+    """with ShaderClock() as sc: <library calls>; sc.ghz() is the shader clock that workgroup 0 of the last
+    statistics kernel (or MFMA probe) saw: cycles of its main loop over 100 MHz reference ticks."""
+
+    def __enter__(self):
+        import torch
+        self.buf = torch.zeros(2, dtype=torch.int64, device="cuda")
+        st = lib().kd_loss_profile_clock(_ptr(self.buf))
+        if st != KD_OK:
+            raise KdLossError(st)
+        return self
+
+    def __exit__(self, *exc):
+        lib().kd_loss_profile_clock(None)
+
+    def ghz(self):
+        c, r = [int(x) for x in self.buf.cpu()]
+        return c / r * 0.1 if r > 0 else float("nan")
 
 
 def probe_mfma_rate(iters=20000, repeats=3):
