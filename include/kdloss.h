@@ -23,8 +23,11 @@
  * TVD and the skewed KLs, whose row value needs both log-sum-exps first).
  *
  * Conventions of every entry point
- *  - plain C ABI; no exceptions, no global state, no allocation, no device
- *    synchronisation.  The caller owns every buffer.
+ *  - plain C ABI; no exceptions, no allocation, no device synchronisation.  The
+ *    caller owns every buffer.  The entry points of this header read no
+ *    environment variable and keep no state from one call to the next, except
+ *    that each kernel's launch attribute is set once per process and device.
+ *    (The measurement aids of kdloss_bench.h keep a per-thread hook.)
  *  - all argument checks run on the host before anything touches the GPU, so
  *    they can be exercised on a machine without one.
  *  - work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
@@ -101,10 +104,22 @@ typedef struct {
                            accumulation over micro-batches, Table 3 caption)        */
   int32_t flags;        /* bit set of kd_flags; other bits must be 0                */
   float teacher_scale;  /* KD_FLAG_TEACHER_FP8 only: > 0, finite                    */
-  int32_t reserved;     /* must be 0                                                */
+  int32_t vocab_chunk;  /* columns of the vocabulary handled per backward chunk (the
+                           width of the dL/dz_s staging buffer): 0 = chosen by the
+                           library, else a multiple of 256 in [256, 2^20].  Enters
+                           the size query and the call alike, so the two cannot
+                           disagree.  Results do not depend on it beyond the
+                           summation order of grad_h_s                              */
+  float loss_scale;     /* finite, non-zero: factor on the loss, the per-token losses
+                           and both gradients (1 = the plain masked mean; e.g. 1 /
+                           micro-batches under gradient accumulation, or the
+                           upstream gradient when it is known before the call)      */
+  int32_t reserved;     /* must be 0 (KD_ERR_PARAM otherwise)                       */
 } kd_loss_params;
 
 /* Bytes of device workspace kd_loss_fwd_bwd needs for these parameters.
+ * (Footnote of Sec. 1: shipping full logits would take about 160 GB per global
+ * batch, 2 T V bytes per T tokens; this is what the recomputation needs instead.)
  * Host only.  The size is O(T * V_c + H_s * V_c + T * (H_t + H_s)) for a vocabulary
  * chunk V_c chosen by the library (a few thousand columns) - staging of dL/dz_s,
  * fp32 sums of grad_h_s, compacted copies of the hidden states - plus copies of
@@ -178,7 +193,8 @@ kd_status kd_loss_fwd_bwd_multi(const kd_loss_params* params, int n_teachers,
                                 float* loss, float* per_token_loss, void* grad_h_s, void* grad_W_s,
                                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Static, NUL-terminated description of a status code. */
+/* Static, NUL-terminated description of a status code (error reporting of this boundary; nothing of
+ * the paper's). */
 const char* kd_status_string(kd_status status);
 
 /* For reports: the vocabulary chunk kd_loss_fwd_bwd uses for these params and the number of kernels
@@ -186,40 +202,6 @@ const char* kd_status_string(kd_status status);
  * workspace).  Either output pointer may be NULL.  Host only. */
 kd_status kd_loss_plan_info(const kd_loss_params* params, int64_t* vocab_chunk,
                             int64_t* n_launches);
-
-/* Benchmark aid (not part of the method): per-kernel timing without a profiler.
- * While a hook is set on the calling thread, every launch of the selected kernel
- * family made by kd_loss_fwd / kd_loss_fwd_bwd on that thread is bracketed by
- * hipEventRecord(events[2i]) before and hipEventRecord(events[2i+1]) after it, on the
- * call's stream, i counting launches since the hook was set, while 2i+1 < n_events.
- * `events` is a host array of hipEvent_t owned by the caller, which must outlive the
- * hook.  which < 0 clears the hook.  Host only; touches no device memory. */
-typedef enum {
-  KD_PROF_STATS = 0,        /* logit tiles + online log-sum-exp (one launch per teacher) */
-  KD_PROF_ROWS = 1,         /* row pass of JSD / TVD / skewed KL (one launch per teacher) */
-  KD_PROF_GRAD = 2,         /* logit tiles + dL/dz_s epilogue (one launch per chunk and teacher) */
-  KD_PROF_GEMM_GRAD_W = 3,  /* grad_W_s product (one launch per chunk)                  */
-  KD_PROF_GEMM_GRAD_H = 4   /* grad_h_s product (one launch per chunk)                  */
-} kd_prof_kernel;
-kd_status kd_loss_profile_hook(int which, void** events, int n_events);
-/* Pairs recorded since the hook was set. */
-int kd_loss_profile_count(void);
-
-/* Benchmark aid, not part of the method: what the bf16 matrix pipe sustains on this GPU with nothing
- * else going on.  One launch of 256 workgroups x 8 waves (the occupancy of the logit kernels), each wave
- * issuing `iters` x 8 independent MFMA 32x32x16 on operands taken from `operands` (device, 128 KiB of
- * bf16 values; the shader clock under this load depends on them, so pass values like real data).
- * Executes KD_PROBE_FLOP_PER_ITER * iters flop.  `sink` (device, 256 * 512 floats) receives sums that
- * only keep the work alive.  Time the launch with events on `hip_stream`. */
-/* Benchmark aid: while set (per host thread; NULL clears it), workgroup 0 of the statistics kernel of
- * kd_loss_fwd / kd_loss_fwd_bwd and of kd_probe_mfma_rate stores into the two int64 at this device
- * address the shader-clock cycles and the 100 MHz reference ticks that its main loop took: their ratio
- * is the shader clock the GPU held under that kernel's load (it is set by the power limit, far below the
- * nominal 2.4 GHz for these kernels).  Host only. */
-kd_status kd_loss_profile_clock(void* two_int64_device);
-
-#define KD_PROBE_FLOP_PER_ITER (256.0 * 8 * 8 * 2 * 32 * 32 * 16)
-kd_status kd_probe_mfma_rate(const void* operands, int iters, float* sink, void* hip_stream);
 
 #ifdef __cplusplus
 }

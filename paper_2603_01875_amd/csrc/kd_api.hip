@@ -1,10 +1,10 @@
 // C ABI of libkdloss: argument checks, workspace planning and the launch sequence.
 // All checks are host-only and happen before the first HIP call.
 #include "../../include/kdloss.h"
+#include "../../include/kdloss_bench.h"
 #include "kd_launch.h"
 
 #include <cmath>
-#include <cstdlib>
 
 namespace {
 
@@ -42,17 +42,24 @@ kd_status check_params(const kd_loss_params* p) {
     if (p->H_t % 128) return KD_ERR_ALIGN;                     // fp8 k-steps are 128 elements
   }
   if (p->w_layout == KD_W_HV && (p->flags & KD_FLAG_TEACHER_FP8)) return KD_ERR_UNSUPPORTED;
+  if (p->vocab_chunk != 0 && (p->vocab_chunk < 256 || p->vocab_chunk > (1 << 20) || p->vocab_chunk % 256))
+    return KD_ERR_PARAM;
+  if (!(std::isfinite(p->loss_scale) && p->loss_scale != 0.f)) return KD_ERR_PARAM;
+  if (p->reserved != 0) return KD_ERR_PARAM;
   return KD_OK;
 }
 
 // Tile counts, vocabulary chunk and split factors.  Depends on the params only.  The per-teacher
-// block is placed at `teacher_base` (default: right after the common part).
-void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward, size_t teacher_base = 0) {
+// block is placed at `teacher_base` (default: right after the common part).  `repack_hv` makes
+// [H][V] heads go through the re-packing path even where they could be read in place (a
+// multi-teacher call takes that decision once for all its teachers).
+void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward, size_t teacher_base = 0,
+          bool repack_hv = false) {
   q.T = (int)p->T; q.V = (int)p->V; q.H_s = (int)p->H_s; q.H_t = (int)p->H_t;
   q.kind = p->kind; q.tau = p->tau; q.beta = p->beta;
   q.grad_f32 = p->grad_dtype == KD_F32;
   q.accumulate_grad_W = p->accumulate_grad_W;
-  q.out_weight = (p->flags & KD_FLAG_TAU2) ? p->tau * p->tau : 1.f;
+  q.out_weight = p->loss_scale * ((p->flags & KD_FLAG_TAU2) ? p->tau * p->tau : 1.f);
   q.accumulate_loss = 0;
   q.n_cu = kd::kNumCU;
   // Operands as the kernels want them: bf16, K-contiguous, K a multiple of 64.  fp32 inputs are
@@ -69,7 +76,7 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward, si
   // [H][V] heads are read in place as k-major operands when they are bf16 with whole k-steps and a
   // vocabulary that the K-contiguous operand of the grad_h_s product can walk in whole 64-element
   // steps; otherwise both are re-packed (transposing) and the kernels see [V][K] copies
-  q.w_hv_inplace = q.w_hv && !q.prep_Wt && !q.prep_Ws && q.V % 64 == 0;
+  q.w_hv_inplace = q.w_hv && !repack_hv && !q.prep_Wt && !q.prep_Ws && q.V % 64 == 0;
   if (q.w_hv && !q.w_hv_inplace) q.prep_Wt = q.prep_Ws = 1;
   // hidden states are also re-packed when a mask is given: valid tokens are compacted to the front
   // (the workspace is sized as if it were, since the size query does not see the mask)
@@ -99,10 +106,7 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward, si
     vc = 8192;
     while (vc > 1024 && (int64_t)q.T_pad * vc * 2 > (512ll << 20)) vc >>= 1;
   }
-  if (const char* e = std::getenv("KD_VOCAB_CHUNK")) {
-    const long v = std::atol(e);
-    if (v >= 256 && v <= (1 << 20)) vc = round_up(v, 256);
-  }
+  if (p->vocab_chunk > 0) vc = p->vocab_chunk;       // the caller's choice (checked: a multiple of 256)
   const int64_t v_all = round_up(q.V, 256);
   if (vc > v_all) vc = v_all;
   q.V_c = (int)vc;
@@ -312,7 +316,7 @@ kd_status run_backward(const Problem* qs, int n_teachers, hipStream_t st) {
 kd_status check_buffers(const kd_loss_params* params, const void* h_t, const void* W_t, const void* h_s,
                         const void* W_s, const uint8_t* mask, float* loss, void* workspace,
                         size_t workspace_bytes, bool backward, void* grad_h_s, void* grad_W_s,
-                        Problem& q, Layout& L, size_t teacher_base = 0) {
+                        Problem& q, Layout& L, size_t teacher_base = 0, bool repack_hv = false) {
   kd_status s = check_params(params);
   if (s != KD_OK) return s;
   if (!h_t || !W_t || !h_s || !W_s || !loss || !workspace) return KD_ERR_NULL;
@@ -320,13 +324,34 @@ kd_status check_buffers(const kd_loss_params* params, const void* h_t, const voi
   if (!aligned16(h_t) || !aligned16(W_t) || !aligned16(h_s) || !aligned16(W_s)) return KD_ERR_ALIGN;
   if (backward && (!aligned16(grad_h_s) || !aligned16(grad_W_s))) return KD_ERR_ALIGN;
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return KD_ERR_ALIGN;
-  plan(params, q, L, backward, teacher_base);
+  plan(params, q, L, backward, teacher_base, repack_hv);
   if (workspace_bytes < L.total) return KD_ERR_WORKSPACE;
   q.h_t = h_t; q.W_t = W_t; q.h_s = h_s; q.W_s = W_s; q.mask = mask;
   q.clock_out = g_clock_out;
   q.loss = loss;
   q.grad_h_s = grad_h_s; q.grad_W_s = grad_W_s;
   carve(q, L, workspace);
+  return KD_OK;
+}
+
+// The student side of a multi-teacher call (how [H][V] heads are read, which student operands are
+// re-packed, where the shared buffers lie) must be the same for every teacher.  Whether [H][V] heads can
+// be read in place depends on each teacher's hidden size, so the decision is taken here once: if any
+// teacher needs the re-packing path, all of them (and the student head) take it.  Also runs the parameter
+// checks of every teacher.
+kd_status multi_student_plan(const kd_loss_params* params, int n_teachers, const int64_t* H_t, bool& repack_hv) {
+  repack_hv = false;
+  for (int k = 0; k < n_teachers; ++k) {
+    kd_loss_params pk = *params;
+    pk.H_t = H_t[k];
+    if (pk.flags & KD_FLAG_TEACHER_FP8) pk.teacher_scale = 1.f;   // checked per teacher by the call itself
+    kd_status s = check_params(&pk);
+    if (s != KD_OK) return s;
+    Problem q{};
+    Layout L{};
+    plan(&pk, q, L, true);
+    if (q.w_hv && !q.w_hv_inplace) repack_hv = true;
+  }
   return KD_OK;
 }
 
@@ -394,16 +419,17 @@ kd_status kd_loss_workspace_size_multi(const kd_loss_params* params, int n_teach
                                        size_t* bytes) {
   if (!bytes || !params || !H_t) return KD_ERR_NULL;
   if (n_teachers < 1 || n_teachers > 16) return KD_ERR_PARAM;
+  bool repack_hv = false;
+  kd_status s = multi_student_plan(params, n_teachers, H_t, repack_hv);
+  if (s != KD_OK) return s;
   size_t base = 0;                       // teacher blocks lie side by side after the common part
   for (int k = 0; k < n_teachers; ++k) {
     kd_loss_params pk = *params;
     pk.H_t = H_t[k];
     if (pk.flags & KD_FLAG_TEACHER_FP8) pk.teacher_scale = 1.f;   // the size does not depend on the scales
-    kd_status s = check_params(&pk);
-    if (s != KD_OK) return s;
     Problem q{};
     Layout L{};
-    plan(&pk, q, L, true, base);
+    plan(&pk, q, L, true, base, repack_hv);
     base = L.total;
   }
   *bytes = base;
@@ -423,6 +449,11 @@ kd_status kd_loss_fwd_bwd_multi(const kd_loss_params* params, int n_teachers, co
   // all checks for all teachers before the first launch
   Problem q[16];
   Layout L[16];
+  bool repack_hv = false;
+  {
+    kd_status s = multi_student_plan(params, n_teachers, H_t, repack_hv);
+    if (s != KD_OK) return s;
+  }
   size_t base = 0;
   for (int k = 0; k < n_teachers; ++k) {
     if (!std::isfinite(weights[k])) return KD_ERR_PARAM;
@@ -431,8 +462,13 @@ kd_status kd_loss_fwd_bwd_multi(const kd_loss_params* params, int n_teachers, co
     if (fp8) pk.teacher_scale = teacher_scales[k];
     q[k] = Problem{};
     kd_status s = check_buffers(&pk, h_t[k], W_t[k], h_s, W_s, mask, loss, workspace, workspace_bytes, true,
-                                grad_h_s, grad_W_s, q[k], L[k], base);
+                                grad_h_s, grad_W_s, q[k], L[k], base, repack_hv);
     if (s != KD_OK) return s;
+    // the backward pass and the student operands are laid out by teacher 0's plan: every teacher must agree
+    if (L[k].common != L[0].common || L[k].dz != L[0].dz || L[k].h_sT != L[0].h_sT || L[k].gh32 != L[0].gh32 ||
+        L[k].prep_h_s != L[0].prep_h_s || L[k].prep_W_s != L[0].prep_W_s || q[k].w_hv_inplace != q[0].w_hv_inplace ||
+        q[k].prep_Ws != q[0].prep_Ws || q[k].prep_hs != q[0].prep_hs || q[k].V_c != q[0].V_c)
+      return KD_ERR_UNSUPPORTED;
     base = L[k].total;
     q[k].per_token_loss = per_token_loss;
     q[k].out_weight *= weights[k];     // scales this teacher's loss and its share of dL/dz_s

@@ -15,6 +15,8 @@
 #include "kd_mfma.hpp"
 #include "kd_launch.h"
 
+#include <atomic>
+
 // tile configurations (overridable for tuning experiments)
 #ifndef KD_LOGIT_CFG
 #define KD_LOGIT_CFG 2, 2, 4, 64, 3     // MI, NI, WN, BK, NST: 128 x 256 tile, 8 waves
@@ -435,7 +437,8 @@ KD_LOGIT_KERNEL void stats_kernel(const LogitArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   SplitWork<TF8, WHV> work(a);
   StatsEpi<KIND> epi(a.c, a.t_scale);
-  const long long c0 = clock64(), r0 = wall_clock64();
+  long long c0 = 0, r0 = 0;
+  if (a.clock_out) { c0 = clock64(); r0 = wall_clock64(); }     // measurement aid, off unless asked for
   tile_loop<2, LCfg, WHV ? 1 : 0, TF8>(work, epi, WHV ? a.V : a.H_s, WHV ? a.V : a.H_t, a.H_s, a.H_t, smem);
   if (a.clock_out && blockIdx.x == 0 && threadIdx.x == 0) {
     a.clock_out[0] = clock64() - c0;
@@ -892,13 +895,23 @@ static int largest_divisor_le(int n, int cap) {
   return 1;
 }
 
-template <class Kern>
-static hipError_t launch_big(Kern kern, int grid, int threads, int smem_bytes, hipStream_t st,
-                             const void* args_ptr) {
-  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes);
+// Launch of a kernel that needs more dynamic LDS than the default limit.  The limit is a property of
+// the kernel on a device: it is raised once per kernel and device (one flag word per instantiation,
+// one bit per device), not on every launch.
+template <auto Kern>
+static hipError_t launch_big(int grid, int threads, int smem_bytes, hipStream_t st, const void* args_ptr) {
+  static std::atomic<uint64_t> attr_done{0};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
+  const uint64_t bit = 1ull << (dev & 63);
+  if (!(attr_done.load(std::memory_order_acquire) & bit)) {
+    e = hipFuncSetAttribute((const void*)Kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes);
+    if (e != hipSuccess) return e;
+    attr_done.fetch_or(bit, std::memory_order_release);
+  }
   void* params[] = {const_cast<void*>(args_ptr)};
-  return hipLaunchKernel((const void*)kern, dim3(grid), dim3(threads), params, smem_bytes, st);
+  return hipLaunchKernel((const void*)Kern, dim3(grid), dim3(threads), params, smem_bytes, st);
 }
 
 static LogitArgs make_logit_args(const Problem& p) {
@@ -921,9 +934,9 @@ hipError_t launch_stats(const Problem& p, hipStream_t st) {
   a.partials = p.partials;
   a.clock_out = p.clock_out;
   const int grid = p.n_tt * p.n_split;      // worst case; workgroups beyond the device-side plan exit
-#define KD_STATS(K) (p.t_fp8 ? launch_big(stats_kernel<K, true, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
-                     : p.w_hv_inplace ? launch_big(stats_kernel<K, false, true>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
-                              : launch_big(stats_kernel<K, false, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a))
+#define KD_STATS(K) (p.t_fp8 ? launch_big<stats_kernel<K, true, false>>(grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
+                     : p.w_hv_inplace ? launch_big<stats_kernel<K, false, true>>(grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
+                              : launch_big<stats_kernel<K, false, false>>(grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a))
   switch (p.kind) {
     case 0: return KD_STATS(0);
     case 1: return KD_STATS(1);
@@ -937,9 +950,9 @@ hipError_t launch_rows(const Problem& p, hipStream_t st) {
   a.vt0 = 0; a.n_vt = p.n_vt;
   a.partials = p.partials;
   const int grid = p.n_tt * p.n_split;
-#define KD_ROWS(K) (p.t_fp8 ? launch_big(rows_kernel<K, true, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
-                    : p.w_hv_inplace ? launch_big(rows_kernel<K, false, true>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
-                             : launch_big(rows_kernel<K, false, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a))
+#define KD_ROWS(K) (p.t_fp8 ? launch_big<rows_kernel<K, true, false>>(grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
+                    : p.w_hv_inplace ? launch_big<rows_kernel<K, false, true>>(grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
+                             : launch_big<rows_kernel<K, false, false>>(grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a))
   switch (p.kind) {
     case 2: return KD_ROWS(2);
     case 3: return KD_ROWS(3);
@@ -982,9 +995,9 @@ hipError_t launch_grad_chunk(const Problem& p, int v0, int width, bool accumulat
   a.dz = (bf16_t*)p.dz; a.ldz = p.V_c;
   const int tiles = p.n_tt * a.n_vt;
   int grid = tiles < p.n_cu ? tiles : p.n_cu;
-#define KD_GRAD(K) (p.t_fp8 ? launch_big(grad_kernel<K, true, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
-                    : p.w_hv_inplace ? launch_big(grad_kernel<K, false, true>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
-                             : launch_big(grad_kernel<K, false, false>, grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a))
+#define KD_GRAD(K) (p.t_fp8 ? launch_big<grad_kernel<K, true, false>>(grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
+                    : p.w_hv_inplace ? launch_big<grad_kernel<K, false, true>>(grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a) \
+                             : launch_big<grad_kernel<K, false, false>>(grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a))
   switch (p.kind) {
     case 0: return KD_GRAD(0);
     case 1: return KD_GRAD(1);
@@ -1021,9 +1034,9 @@ hipError_t launch_gemm(const GemmDesc& d, int n_cu, hipStream_t st) {
   a.k_rows = d.k_rows;
   const int tiles = a.n_mt * a.n_nt * a.n_ksplit;       // worst case (no token masked)
   const int grid = tiles < n_cu ? tiles : n_cu;
-  if (d.k_major == 0) return launch_big(gemm_kernel<0>, grid, GCfg::NT, GCfg::SMEM_BYTES, st, &a);
-  if (d.k_major == 1) return launch_big(gemm_kernel<1>, grid, GCfg::NT, GCfg::SMEM_BYTES, st, &a);
-  if (d.k_major == 2) return launch_big(gemm_kernel<2>, grid, GCfg::NT, GCfg::SMEM_BYTES, st, &a);
+  if (d.k_major == 0) return launch_big<gemm_kernel<0>>(grid, GCfg::NT, GCfg::SMEM_BYTES, st, &a);
+  if (d.k_major == 1) return launch_big<gemm_kernel<1>>(grid, GCfg::NT, GCfg::SMEM_BYTES, st, &a);
+  if (d.k_major == 2) return launch_big<gemm_kernel<2>>(grid, GCfg::NT, GCfg::SMEM_BYTES, st, &a);
   return hipErrorInvalidValue;
 }
 

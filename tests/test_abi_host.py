@@ -12,30 +12,36 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared_symbols():
-    src = open(os.path.join(ROOT, "include", "kdloss.h")).read()
-    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(kd_[a-z_]+)\s*\(", src)))
+    """Every function declared in any header under include/."""
+    import glob
+    names = set()
+    for h in glob.glob(os.path.join(ROOT, "include", "*.h")):
+        src = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        names |= set(re.findall(r"\b(kd_[a-z0-9_]+)\s*\(", src))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
     names = _declared_symbols()
     assert {"kd_loss_workspace_size", "kd_loss_fwd_bwd", "kd_loss_fwd", "kd_status_string",
-            "kd_loss_plan_info"} <= set(names)
+            "kd_loss_plan_info", "kd_loss_fwd_bwd_multi", "kd_quantize_e4m3", "kd_loss_profile_hook",
+            "kd_probe_mfma_rate"} <= set(names)
     L = K.lib()
     for n in names:
         assert hasattr(L, n), n
 
 
-def test_header_is_plain_c():
-    """The boundary is a C ABI: the header must compile as C99 on its own."""
+@pytest.mark.parametrize("header", ["kdloss.h", "kdloss_bench.h"])
+def test_header_is_plain_c(header):
+    """The boundary is a C ABI: each header must compile as C99 on its own."""
     import subprocess
     r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-x", "c",
-                        os.path.join(ROOT, "include", "kdloss.h")], capture_output=True, text=True)
+                        os.path.join(ROOT, "include", header)], capture_output=True, text=True)
     assert r.returncode == 0, r.stderr
 
 
 def test_struct_layout_matches_header():
-    assert ctypes.sizeof(K.KdLossParams) == 4 * 8 + 10 * 4          # 72 bytes, no padding
+    assert ctypes.sizeof(K.KdLossParams) == 4 * 8 + 12 * 4          # 80 bytes, no padding
 
 
 def test_status_strings():
@@ -80,6 +86,10 @@ def test_workspace_is_far_below_T_times_V():
     (dict(flags=K.FLAG_TEACHER_FP8, teacher_scale=1.0, in_dtype=K.F32), 6),
     (dict(flags=K.FLAG_TEACHER_FP8, teacher_scale=1.0, H_t=4160), 3),
     (dict(flags=8), 4),
+    # vocabulary chunk: 0 or a multiple of 256 in [256, 2^20]; loss scale: finite, non-zero; reserved: 0
+    (dict(vocab_chunk=100), 4), (dict(vocab_chunk=-256), 4), (dict(vocab_chunk=1000), 4),
+    (dict(vocab_chunk=(1 << 20) + 256), 4), (dict(loss_scale=0.0), 4), (dict(loss_scale=float("inf")), 4),
+    (dict(loss_scale=float("nan")), 4),
 ])
 def test_bad_params_are_rejected(kw, status):
     with pytest.raises(K.KdLossError) as e:
@@ -153,3 +163,110 @@ def test_quantize_argument_checks():
     assert L.kd_quantize_e4m3(a, K.BF16, 16, 0.0, b, None) == 4
     assert L.kd_quantize_e4m3(a, K.BF16, 16, float("nan"), b, None) == 4
     assert L.kd_quantize_e4m3(ctypes.c_void_p(0x1004), K.BF16, 16, 1.0, b, None) == 3
+
+
+def test_reserved_word_must_be_zero():
+    p = _ws()
+    p.reserved = 1
+    with pytest.raises(K.KdLossError) as e:
+        K.kd_loss_workspace_size(p)
+    assert e.value.status == 4
+
+
+def test_vocab_chunk_enters_the_size_query_and_the_plan():
+    """The chunk is a field of the parameter block (no environment variable): the size query, the plan
+    report and the call all see the same value."""
+    auto = _ws()
+    vc_auto, n_auto = K.kd_loss_plan_info(auto)
+    assert vc_auto == 16384
+    small = _ws(vocab_chunk=2048)
+    vc, n = K.kd_loss_plan_info(small)
+    assert vc == 2048 and n > n_auto
+    assert K.kd_loss_workspace_size(small) < K.kd_loss_workspace_size(auto)
+    os.environ["KD_VOCAB_CHUNK"] = "512"          # the library reads no environment variable
+    try:
+        assert K.kd_loss_plan_info(auto)[0] == 16384
+    finally:
+        del os.environ["KD_VOCAB_CHUNK"]
+    # a chunk wider than the vocabulary is clamped to it
+    assert K.kd_loss_plan_info(K.make_params(512, 256, 128, 4096, vocab_chunk=1 << 20))[0] == 4096
+    # a call with a workspace sized for another chunk is refused on the host
+    n_small = K.kd_loss_workspace_size(small)
+    good = [ctypes.c_void_p(0x1000 * (i + 1)) for i in range(10)]
+    assert K.lib().kd_loss_fwd_bwd(ctypes.byref(auto), *good, ctypes.c_size_t(n_small), None) == 5
+
+
+def test_multi_teacher_hidden_major_heads_share_one_student_plan():
+    """[H,V] heads, one teacher on the 64-element grid and one off it: the student side must be planned
+    once for the whole call (all heads re-packed), so the workspace holds one copy of the student head and
+    one of each teacher head."""
+    base = dict(T=512, H_s=128, V=4096, w_layout=K.W_HV)
+
+    def size(hts):
+        p = K.make_params(H_t=hts[0], **base)
+        H = (ctypes.c_int64 * len(hts))(*hts)
+        n = ctypes.c_size_t(0)
+        assert K.lib().kd_loss_workspace_size_multi(ctypes.byref(p), len(hts), H, ctypes.byref(n)) == 0
+        return n.value
+
+    inplace = size([128, 256])
+    mixed = size([128, 200])
+    # every head copied: student 4096 x 128, teachers 4096 x 128 and 4096 x 256 (200 padded to 256), bf16
+    assert mixed >= inplace + 2 * 4096 * (128 + 128 + 256)
+    assert size([200, 128]) == mixed                       # whichever teacher needs it
+
+
+def _cpu_ops(T=6, H_t=16, H_s=8, V=24, dtype=None):
+    import torch
+    dtype = dtype or torch.bfloat16
+    return (torch.zeros(T, H_t, dtype=dtype), torch.zeros(V, H_t, dtype=dtype), torch.zeros(T, H_s, dtype=dtype),
+            torch.zeros(V, H_s, dtype=dtype))
+
+
+def test_wrapper_checks_operands_before_any_call():
+    """The C ABI sees only addresses; dtype, shape, contiguity and device are checked by the binding."""
+    import torch
+    h_t, W_t, h_s, W_s = _cpu_ops()
+    ok = K.check_operands(h_t, W_t, h_s, W_s, require_cuda=False)
+    assert ok == (6, 16, 8, 24, K.BF16, K.BF16)
+    with pytest.raises(ValueError, match="CUDA"):
+        K.check_operands(h_t, W_t, h_s, W_s)                                  # CPU tensors
+    with pytest.raises(ValueError, match="CUDA"):
+        K.kd_loss_fwd_bwd(h_t, W_t, h_s, W_s)                                 # ... through the wrapper too
+    bad = [
+        dict(h_s=h_s.to(torch.float16), W_s=W_s.to(torch.float16)),           # fp16 is not a supported dtype
+        dict(W_s=W_s.float()),                                                # student dtypes differ
+        dict(h_t=h_t.float()),                                                # teacher dtype differs
+        dict(h_s=h_s[:5]),                                                    # token counts differ
+        dict(W_s=torch.zeros(25, 8, dtype=torch.bfloat16)),                   # vocabularies differ
+        dict(W_t=torch.zeros(24, 17, dtype=torch.bfloat16)),                  # hidden size differs
+        dict(W_t=W_t.t()),                                                    # wrong layout / not contiguous
+        dict(h_t=torch.zeros(6, 32, dtype=torch.bfloat16)[:, ::2]),           # not contiguous
+        dict(h_t=h_t.reshape(-1)),                                            # not 2-D
+        dict(mask=torch.ones(6, dtype=torch.int64)),                          # 8-byte mask elements
+        dict(mask=torch.ones(5, dtype=torch.uint8)),                          # wrong mask length
+        dict(grad_W_s=torch.zeros(24, 8, dtype=torch.float32)),               # gradient buffer of the wrong dtype
+        dict(grad_W_s=torch.zeros(8, 24, dtype=torch.bfloat16)),              # ... or shape
+        dict(flags=K.FLAG_TEACHER_FP8),                                       # fp8 teacher needs uint8 codes
+    ]
+    for kw in bad:
+        args = dict(h_t=h_t, W_t=W_t, h_s=h_s, W_s=W_s)
+        args.update(kw)
+        with pytest.raises(ValueError):
+            K.check_operands(require_cuda=False, **args)
+    # [H,V] layout and the fp8 teacher, accepted
+    assert K.check_operands(h_t, W_t.t().contiguous(), h_s, W_s.t().contiguous(), w_layout=K.W_HV,
+                            require_cuda=False)[3] == 24
+    q = torch.zeros(6, 16, dtype=torch.uint8), torch.zeros(24, 16, dtype=torch.uint8)
+    assert K.check_operands(q[0], q[1], h_s, W_s, flags=K.FLAG_TEACHER_FP8, mask=torch.ones(6, dtype=torch.bool),
+                            require_cuda=False)[0] == 6
+
+
+def test_thin_calls_check_sizes_against_the_parameter_block():
+    import torch
+    h_t, W_t, h_s, W_s = _cpu_ops()
+    p = K.make_params(6, 16, 8, 24)
+    loss = torch.zeros(1)
+    with pytest.raises(ValueError):
+        K.kd_loss_fwd_bwd_raw(p, h_t, W_t, h_s, W_s, None, loss, None, torch.zeros(6, 8), torch.zeros(24, 8),
+                              torch.zeros(1024, dtype=torch.uint8))

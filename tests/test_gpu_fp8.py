@@ -18,12 +18,7 @@ pytestmark = pytest.mark.gpu
 FP8_TIE_GAP = 3e-4
 
 
-@pytest.fixture(autouse=True)
-def _chunk_env(monkeypatch):
-    monkeypatch.delenv("KD_VOCAB_CHUNK", raising=False)
-
-
-def _run_fp8(cfg, data, f8, forward_only=False):
+def _run_fp8(cfg, data, f8, forward_only=False, **more):
     import torch
     from paper_2603_01875_amd import kdloss as K
     q_h = torch.from_numpy(f8["q_h_t"]).cuda()
@@ -31,7 +26,8 @@ def _run_fp8(cfg, data, f8, forward_only=False):
     h_s = G.to_device(data["h_s"], cfg.dtype)
     W_s = G.to_device(data["W_s"], cfg.dtype)
     mask = None if data["mask"] is None else torch.from_numpy(data["mask"]).cuda()
-    kw = dict(tau=cfg.tau, kind=cfg.kind, beta=cfg.beta, flags=K.FLAG_TEACHER_FP8, teacher_scale=f8["teacher_scale"])
+    kw = dict(tau=cfg.tau, kind=cfg.kind, beta=cfg.beta, flags=K.FLAG_TEACHER_FP8, teacher_scale=f8["teacher_scale"],
+              **more)
     out = (K.kd_loss_fwd if forward_only else K.kd_loss_fwd_bwd)(q_h, q_W, h_s, W_s, mask, **kw)
     torch.cuda.synchronize()
     return out
@@ -66,13 +62,12 @@ KINDS = [("fkl_bf16", I.FKL, 0.5), ("rkl_bf16", I.RKL, 0.5), ("jsd_bf16", I.JSD,
 
 
 @pytest.mark.parametrize("name,kind,beta", KINDS)
-def test_fp8_teacher_ragged_multi_tile(name, kind, beta, monkeypatch):
+def test_fp8_teacher_ragged_multi_tile(name, kind, beta):
     # 3 token tiles (last one ragged), 20 vocabulary tiles (last one 8 rows), 5 chunks, 3 fp8 k-steps
-    monkeypatch.setenv("KD_VOCAB_CHUNK", "512")
     cfg = I.scaled(I.workload(name), batch=3, seq=200, H_t=384, H_s=128, V=2440)
     data = I.generate(cfg)
     f8 = G.fp8_teacher(data)
-    out = _run_fp8(cfg, data, f8)
+    out = _run_fp8(cfg, data, f8, vocab_chunk=512)
     G.check(out, _oracle_fp8(cfg, data, f8), name + " fp8 teacher")
     keep = data["mask"].astype(bool)
     assert (G.to_host(out["grad_h_s"])[~keep] == 0).all()
@@ -132,13 +127,12 @@ def test_codes_that_bf16_holds_exactly_give_the_bf16_result():
     assert np.abs(ga - gb).max() <= 2e-2 * np.abs(gb).max()
 
 
-def test_two_fp8_teachers_with_their_own_scales(monkeypatch):
+def test_two_fp8_teachers_with_their_own_scales():
     """Multi-teacher call with fp8 teachers: each teacher has its own joint scale; against the oracle on
     the de-quantised teachers."""
     import torch
     from oracle import kd_oracle as O
     from paper_2603_01875_amd import kdloss as K
-    monkeypatch.setenv("KD_VOCAB_CHUNK", "512")
     base = I.scaled(I.workload("fkl_bf16"), batch=2, seq=150, H_s=128, V=1544)
     ds = [I.generate(I.scaled(base, H_t=h, w_t_std=sd, seed=900 + i)) for i, (h, sd) in enumerate(((128, 0.02), (256, 0.05)))]
     f8 = [G.fp8_teacher(d) for d in ds]
@@ -152,6 +146,7 @@ def test_two_fp8_teachers_with_their_own_scales(monkeypatch):
                                       [torch.from_numpy(f["q_W_t"]).cuda() for f in f8], weights,
                                       G.to_device(h_s, I.BF16), G.to_device(W_s, I.BF16),
                                       torch.from_numpy(mask).cuda(), tau=base.tau, kind=kind, beta=beta,
-                                      flags=K.FLAG_TEACHER_FP8, teacher_scales=[f["teacher_scale"] for f in f8])
+                                      flags=K.FLAG_TEACHER_FP8, teacher_scales=[f["teacher_scale"] for f in f8],
+                                      vocab_chunk=512)
         torch.cuda.synchronize()
         G.check(out, ref, f"two fp8 teachers kind={kind}")

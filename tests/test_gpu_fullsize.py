@@ -1,6 +1,16 @@
-"""Parity at the benchmark's full size and launch configuration (fkl_bf16: T=4096, H_t=4096,
-H_s=1024, V=151936) on outputs the oracle can compute one by one, plus properties that hold at
-any size; and a medium problem (many tiles, splits and chunks) against the complete oracle."""
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+Every element of every output (loss, all per-token losses, all of grad_h_s, all of grad_W_s) is
+compared with the complete fp64 oracle for fkl_bf16 (the headline), rkl_bf16, jsd_bf16 and
+large_teacher at their full sizes.  long_peaked (T = 32768) would cost the oracle 173 TFLOP in
+fp64 (a quarter of an hour on the host), so it is checked in two parts: its first 2048 tokens as a
+problem of its own (full V and H, the vocabulary chunk of the full-size plan), every element; and
+the full-T launch on sampled token rows that the oracle computes one by one.  Sampled rows of
+grad_W_s at full T would need the log-sum-exps of all 32768 rows (92 TFLOP in fp64) and are not
+checked there.
+"""
+import time
+
 import numpy as np
 import pytest
 
@@ -17,6 +27,53 @@ def test_medium_problem_full_oracle(name):
     data = I.generate(cfg)
     out = G.run_gpu(cfg, data)
     G.check(out, G.run_oracle(cfg, data), f"medium {name}")
+
+
+def _every_element(name, cfg, data, **kw):
+    t0 = time.perf_counter()
+    out = G.run_gpu(cfg, data, **kw)
+    ws_bytes = out["workspace"].numel()
+    t1 = time.perf_counter()
+    ref = G.run_oracle(cfg, data)
+    t2 = time.perf_counter()
+    rel = G.check(out, ref, name)
+    print(f"[{name}] T={cfg.T} V={cfg.V}: GPU call {t1 - t0:.1f} s, oracle {t2 - t1:.1f} s, compare "
+          f"{time.perf_counter() - t2:.1f} s, loss {ref['loss']:.6f} (rel err {rel:.1e}), n={ref['n']}", flush=True)
+    assert ws_bytes < 0.35 * 2 * cfg.T * cfg.V            # never a [T, V] buffer
+    return out, ref
+
+
+@pytest.mark.parametrize("name", ["fkl_bf16", "rkl_bf16", "jsd_bf16", "large_teacher"])
+def test_full_size_every_element(name):
+    """The complete oracle on the complete workload; nothing rests on a sum or a norm."""
+    cfg = I.workload(name)
+    data = I.generate(cfg)
+    out, ref = _every_element(name, cfg, data)
+    if name == "fkl_bf16":
+        assert abs(ref["loss"] - 1.02) < 0.03              # Gaussian-regime value (sigma_t^2 + sigma_s^2) / 2
+    keep = data["mask"].astype(bool)
+    assert (G.to_host(out["grad_h_s"])[~keep] == 0).all()  # masked tokens: exactly zero rows
+    assert (G.to_host(out["per_token_loss"])[~keep] == 0).all()
+
+
+@pytest.fixture(scope="module")
+def long_peaked():
+    cfg = I.workload("long_peaked")
+    return cfg, I.generate(cfg)
+
+
+def test_long_peaked_first_2048_tokens_every_element(long_peaked):
+    """T = 2048 rows of the long-sequence workload as a self-contained problem (full V, H_t, H_s), with the
+    vocabulary chunk the library uses at the full T = 32768, against the complete oracle."""
+    from paper_2603_01875_amd import kdloss as K
+    full_cfg, full = long_peaked
+    vc_full, _ = K.kd_loss_plan_info(K.make_params(full_cfg.T, full_cfg.H_t, full_cfg.H_s, full_cfg.V,
+                                                    full_cfg.kind, full_cfg.tau, full_cfg.beta))
+    cfg = I.scaled(full_cfg, seq=2048)
+    data = dict(h_t=full["h_t"][:2048], h_s=full["h_s"][:2048], W_t=full["W_t"], W_s=full["W_s"],
+                mask=full["mask"][:2048])
+    _, ref = _every_element("long_peaked[:2048]", cfg, data, vocab_chunk=vc_full)
+    assert (ref["per_token_loss"] <= 0.3251 + 1e-9).all()  # JSD_0.1 <= H(0.1), near one-hot teacher
 
 
 def _sampled_rows_check(cfg, data, out, rows):
@@ -46,78 +103,26 @@ def torch_index(rows):
     return torch.from_numpy(np.asarray(rows, dtype=np.int64)).cuda()
 
 
-def _properties(cfg, data, out):
-    """Checks that hold at any size (see the headline test for what each one pins)."""
+def test_long_peaked_full_T_sampled_token_rows(long_peaked):
+    """The full T = 32768 launch: per-token loss and grad_h_s of sampled tokens (first, last, tile borders,
+    random ones) against the oracle, every output finite, and the mean of the per-token losses."""
     import torch
-    mask = data["mask"].astype(bool)
-    ptl = out["per_token_loss"].double().cpu().numpy()
-    loss = float(out["loss"].item())
-    assert abs(loss - ptl[mask].mean()) <= 1e-5 * abs(loss)
-    gh = out["grad_h_s"]
-    if (~mask).any():
-        assert not gh[torch.from_numpy(~mask).cuda()].any()
-    gW = out["grad_W_s"]
-    scale = gW.abs().max().item()
-    colsum = gW.sum(dim=0, dtype=torch.float32).abs().max().item()
-    assert colsum <= 2e-2 * scale * np.sqrt(cfg.V)
-    h_s = G.to_device(data["h_s"], cfg.dtype); W_s = G.to_device(data["W_s"], cfg.dtype)
-    a = torch.dot(gh.flatten().double(), h_s.flatten().double()).item()
-    b = sum(torch.dot(gW[v0:v0 + 32768].flatten().double(), W_s[v0:v0 + 32768].flatten().double()).item()
-            for v0 in range(0, cfg.V, 32768))
-    assert abs(a - b) <= 2e-2 * max(abs(a), abs(b))
-    assert torch.isfinite(gW[-1]).all() and gW[-1].abs().max().item() > 0
-
-
-@pytest.mark.parametrize("name", ["large_teacher", "long_peaked"])
-def test_other_full_size_workloads(name):
-    """The two largest benchmark shapes at full size: sampled rows against the oracle + properties."""
-    cfg = I.workload(name)
-    data = I.generate(cfg)
+    cfg, data = long_peaked
     out = G.run_gpu(cfg, data)
-    mask = data["mask"].astype(bool)
-    rows = np.array([0, 255, 256, cfg.T // 2 + 1, cfg.T - 1] + list(np.flatnonzero(~mask)[:2]))
+    rng = np.random.default_rng(5)
+    rows = np.array([0, 255, 256, cfg.T // 2 + 1, cfg.T - 257, cfg.T - 1] + list(rng.integers(0, cfg.T, 10)))
     l = _sampled_rows_check(cfg, data, out, rows)
-    if name == "long_peaked":        # near one-hot teacher: JSD_0.1 stays below its bound H(0.1)
-        assert (l <= 0.3251 + 1e-6).all() and np.isfinite(G.to_host(out["per_token_loss"])).all()
-    _properties(cfg, data, out)
-
-
-def test_headline_workload_sampled_outputs_and_properties():
-    import torch
-    cfg = I.workload("fkl_bf16")
-    data = I.generate(cfg)
-    out = G.run_gpu(cfg, data)
-    mask = data["mask"].astype(bool)
-    # (1) sampled rows, computed by the oracle one by one: valid, masked, first, last, tile borders
-    rows = np.array([0, 1, 255, 256, 257, 1023, 1024, 2047, 2048, 3000, 4095] + list(np.flatnonzero(~mask)[:3]))
-    _sampled_rows_check(cfg, data, out, rows)
-    # (2) the scalar loss is the masked mean of the per-token losses (sampled rows pin those)
-    ptl = G.to_host(out["per_token_loss"])
+    assert (l <= 0.3251 + 1e-6).all()
+    ptl = out["per_token_loss"].double()
+    assert torch.isfinite(ptl).all() and float(ptl.max()) <= 0.3251 + 1e-5 and float(ptl.min()) >= 0.0
     loss = float(out["loss"].item())
-    assert abs(loss - ptl[mask].mean()) <= 1e-5 * abs(loss)
-    assert abs(loss - 1.02) < 0.03                 # Gaussian-regime value (sigma_t^2 + sigma_s^2)/2
-    # (3) masked rows: exactly zero gradient rows
-    gh = out["grad_h_s"].float()
-    assert not gh[torch.from_numpy(~mask).cuda()].any()
-    # (4) every dz row sums to zero => column sums of grad_W_s vanish
-    gW = out["grad_W_s"].float()
-    scale = gW.abs().max().item()
-    assert gW.sum(dim=0).abs().max().item() <= 2e-2 * scale * np.sqrt(cfg.V)
-    # (5) <grad_h_s, h_s> == <grad_W_s, W_s> (both are sum dz * z_s): ties grad_W_s to the pinned grad_h_s
-    h_s = G.to_device(data["h_s"], cfg.dtype).float(); W_s = G.to_device(data["W_s"], cfg.dtype).float()
-    a = (gh.double() * h_s.double()).sum().item()
-    b = (gW.double() * W_s.double()).sum().item()
-    assert abs(a - b) <= 2e-2 * max(abs(a), abs(b))
-    # (6) sampled vocabulary rows of grad_W_s against dz columns rebuilt from the oracle's row
-    #     log-sum-exps on a token subset is not possible without all rows; instead check a chunk
-    #     border and the ragged last tile are written (non-zero, finite)
-    for v in (0, 16383, 16384, 151935):
-        assert torch.isfinite(gW[v]).all() and gW[v].abs().max().item() > 0
+    assert abs(loss - float(ptl.mean())) <= 1e-5 * abs(loss)
+    assert torch.isfinite(out["grad_h_s"]).all() and torch.isfinite(out["grad_W_s"]).all()
 
 
 def test_headline_workload_with_fp8_teacher():
-    """The benchmark's optional fp8 mode at full size: sampled rows against the oracle on the
-    de-quantised teacher, and the size-independent properties."""
+    """The benchmark's optional fp8 mode at full size, against the complete oracle on the de-quantised
+    teacher (the exact values the e4m3 codes stand for)."""
     import torch
     from paper_2603_01875_amd import kdloss as K
     cfg = I.workload("fkl_bf16")
@@ -129,8 +134,5 @@ def test_headline_workload_with_fp8_teacher():
                             flags=K.FLAG_TEACHER_FP8, teacher_scale=f8["teacher_scale"])
     torch.cuda.synchronize()
     d = dict(data); d["h_t"], d["W_t"] = f8["h_t"], f8["W_t"]
-    mask = data["mask"].astype(bool)
-    rows = np.array([0, 255, 256, 2047, 2048, 4095] + list(np.flatnonzero(~mask)[:2]))
-    _sampled_rows_check(cfg, d, out, rows)
-    _properties(cfg, data, out)
+    G.check(out, G.run_oracle(cfg, d), "fkl_bf16 with fp8 teacher")
     assert abs(float(out["loss"].item()) - 1.02) < 0.03

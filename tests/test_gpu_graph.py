@@ -11,15 +11,14 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("kind,beta", [(I.FKL, 0.5), (I.JSD, 0.3)])
-def test_captured_call_replays_bit_exactly(kind, beta, monkeypatch):
+def test_captured_call_replays_bit_exactly(kind, beta):
     import torch
     from paper_2603_01875_amd import kdloss as K
-    monkeypatch.setenv("KD_VOCAB_CHUNK", "512")
     cfg = I.scaled(I.workload("fkl_bf16"), batch=2, seq=200, H_t=192, H_s=128, V=1544, kind=kind, beta=beta)
     data = I.generate(cfg)
     d = {k: G.to_device(data[k], cfg.dtype) for k in ("h_t", "W_t", "h_s", "W_s")}
     mask = torch.from_numpy(data["mask"]).cuda()
-    p = K.make_params(cfg.T, cfg.H_t, cfg.H_s, cfg.V, kind, cfg.tau, beta)
+    p = K.make_params(cfg.T, cfg.H_t, cfg.H_s, cfg.V, kind, cfg.tau, beta, vocab_chunk=512)
     ws = K.alloc_workspace(p)
     outs = [dict(loss=torch.zeros(1, device="cuda"), ptl=torch.zeros(cfg.T, device="cuda"),
                  gh=torch.zeros(cfg.T, cfg.H_s, device="cuda", dtype=torch.bfloat16),

@@ -1,8 +1,6 @@
 """GPU parity: the HIP path, called through the C ABI, against the fp64 oracle on the
 same seeded inputs.  Sizes span several tiles in both directions with ragged tails and
 several vocabulary chunks, yet the oracle finishes in seconds."""
-import os
-
 import numpy as np
 import pytest
 
@@ -14,18 +12,12 @@ pytestmark = pytest.mark.gpu
 KINDS = [("fkl_bf16", I.FKL, 0.5), ("rkl_bf16", I.RKL, 0.5), ("jsd_bf16", I.JSD, 0.5), ("long_peaked", I.JSD, 0.1)]
 
 
-@pytest.fixture(autouse=True)
-def _chunk_env(monkeypatch):
-    monkeypatch.delenv("KD_VOCAB_CHUNK", raising=False)
-
-
 @pytest.mark.parametrize("name,kind,beta", KINDS)
-def test_ragged_multi_tile(name, kind, beta, monkeypatch):
+def test_ragged_multi_tile(name, kind, beta):
     # 3 token tiles (last one ragged), 20 vocabulary tiles (last one 8 rows), 5 chunks
-    monkeypatch.setenv("KD_VOCAB_CHUNK", "512")
     cfg = I.scaled(I.workload(name), batch=3, seq=200, H_t=192, H_s=128, V=2440)
     data = I.generate(cfg)
-    out = G.run_gpu(cfg, data)
+    out = G.run_gpu(cfg, data, vocab_chunk=512)
     G.check(out, G.run_oracle(cfg, data), name)
     keep = data["mask"].astype(bool)
     gh = G.to_host(out["grad_h_s"])
@@ -42,12 +34,11 @@ def test_temperature(name, kind, beta, tau):
     G.check(G.run_gpu(cfg, data), G.run_oracle(cfg, data), f"{name} tau={tau}")
 
 
-def test_single_chunk_equals_many_chunks(monkeypatch):
+def test_single_chunk_equals_many_chunks():
     cfg = I.scaled(I.workload("fkl_bf16"), batch=2, seq=128, H_t=128, H_s=128, V=1536)
     data = I.generate(cfg)
     a = G.run_gpu(cfg, data)
-    monkeypatch.setenv("KD_VOCAB_CHUNK", "256")
-    b = G.run_gpu(cfg, data)
+    b = G.run_gpu(cfg, data, vocab_chunk=256)
     ref = G.run_oracle(cfg, data)
     G.check(a, ref, "one chunk"); G.check(b, ref, "six chunks")
     assert float(a["loss"].item()) == float(b["loss"].item())           # forward does not depend on chunking
@@ -80,6 +71,21 @@ def test_fp32_gradients_and_accumulation():
     gw = a["grad_W_s"].clone()
     b = G.run_gpu(cfg, data, grad_dtype=K.F32, grad_W_s=gw, accumulate_grad_W=True)
     assert torch.allclose(b["grad_W_s"], 2 * a["grad_W_s"], rtol=1e-6, atol=0)
+    # accumulation onto unrelated prior content, against the oracle's gradient plus that content
+    rng = np.random.default_rng(5)
+    prior = (rng.standard_normal(ref["grad_W_s"].shape) * np.abs(ref["grad_W_s"]).max()).astype(np.float32)
+    c = G.run_gpu(cfg, data, grad_dtype=K.F32, grad_W_s=torch.from_numpy(prior).cuda(), accumulate_grad_W=True)
+    G.check(c, dict(ref, grad_W_s=ref["grad_W_s"] + prior.astype(np.float64)), "accumulate onto prior content")
+
+
+def test_loss_scale_multiplies_loss_and_gradients():
+    cfg = I.scaled(I.workload("rkl_bf16"), batch=2, seq=100, H_t=64, H_s=64, V=512)
+    data = I.generate(cfg)
+    ref = G.run_oracle(cfg, data)
+    scaled = {k: (0.125 * v if k != "n" else v) for k, v in ref.items()}      # e.g. 1 / 8 micro-batches
+    G.check(G.run_gpu(cfg, data, loss_scale=0.125), scaled, "loss_scale = 1/8")
+    neg = {k: (-3.0 * v if k != "n" else v) for k, v in ref.items()}
+    G.check(G.run_gpu(cfg, data, loss_scale=-3.0), neg, "loss_scale = -3")
 
 
 def test_forward_only_matches():
@@ -92,6 +98,12 @@ def test_forward_only_matches():
     f = K.kd_loss_fwd(d["h_t"], d["W_t"], d["h_s"], d["W_s"], torch.from_numpy(data["mask"]).cuda(),
                       tau=cfg.tau, kind=cfg.kind, beta=cfg.beta)
     assert torch.equal(f["loss"], full["loss"]) and torch.equal(f["per_token_loss"], full["per_token_loss"])
+    # ... and both against the oracle
+    ref = G.run_oracle(cfg, data)
+    G.check(full, ref, "full call")
+    assert abs(float(f["loss"].item()) - ref["loss"]) <= G.LOSS_RTOL * abs(ref["loss"])
+    ptl = G.to_host(f["per_token_loss"])
+    assert np.abs(ptl - ref["per_token_loss"]).max() <= 2e-3 * np.abs(ref["per_token_loss"]).max() + 5e-7
 
 
 def test_peaked_teacher_is_stable():
@@ -130,12 +142,11 @@ def test_fp32_inputs_other_kinds():
 
 @pytest.mark.parametrize("kind,w", [(I.TVD, 0.5), (I.SKEW_FKL, 0.1), (I.SKEW_RKL, 0.1), (I.SKEW_FKL, 0.7)])
 @pytest.mark.parametrize("name", ["fkl_bf16", "rkl_bf16"])       # mild and sharper teacher
-def test_tvd_and_skewed_kl(name, kind, w, monkeypatch):
-    monkeypatch.setenv("KD_VOCAB_CHUNK", "1024")
+def test_tvd_and_skewed_kl(name, kind, w):
     cfg = I.scaled(I.workload(name), batch=2, seq=200, H_t=192, H_s=128, V=2440, kind=kind, beta=w, tau=1.3)
     data = I.generate(cfg)
     extra = G.tvd_tie_allowance(cfg, data) if kind == I.TVD else None      # near-ties: either sign is valid
-    G.check(G.run_gpu(cfg, data), G.run_oracle(cfg, data), f"{name} kind={kind} w={w}", extra)
+    G.check(G.run_gpu(cfg, data, vocab_chunk=1024), G.run_oracle(cfg, data), f"{name} kind={kind} w={w}", extra)
 
 
 def test_tvd_peaked_teacher():
@@ -188,13 +199,12 @@ def test_multi_teacher_and_tau2():
 
 
 @pytest.mark.parametrize("name,kind,beta", KINDS)
-def test_heads_stored_hidden_major(name, kind, beta, monkeypatch):
+def test_heads_stored_hidden_major(name, kind, beta):
     """KD_W_HV: W_t [H_t, V], W_s [H_s, V] and grad_W_s [H_s, V], read and written in place.  Against the
     oracle in the same storage order, and against the library's own [V, H] result."""
     import torch
     from oracle import kd_oracle as O
     from paper_2603_01875_amd import kdloss as K
-    monkeypatch.setenv("KD_VOCAB_CHUNK", "512")
     # 3 token tiles (ragged, masked tails), 13 vocabulary tiles (last one 64 rows), 4 chunks (last one 192 wide)
     cfg = I.scaled(I.workload(name), batch=3, seq=200, H_t=192, H_s=128, V=1600)
     data = I.generate(cfg)
@@ -205,23 +215,22 @@ def test_heads_stored_hidden_major(name, kind, beta, monkeypatch):
     dev = lambda x: G.to_device(x, I.BF16)
     mask = torch.from_numpy(data["mask"]).cuda()
     out = K.kd_loss_fwd_bwd(dev(data["h_t"]), dev(hv["W_t"]), dev(data["h_s"]), dev(hv["W_s"]), mask, tau=cfg.tau,
-                            kind=kind, beta=beta, w_layout=K.W_HV)
+                            kind=kind, beta=beta, w_layout=K.W_HV, vocab_chunk=512)
     torch.cuda.synchronize()
     assert tuple(out["grad_W_s"].shape) == (cfg.H_s, cfg.V)
     G.check(out, ref, name + " [H,V] heads")
-    vh = G.run_gpu(cfg, data)
+    vh = G.run_gpu(cfg, data, vocab_chunk=512)
     assert float(out["loss"].item()) == pytest.approx(float(vh["loss"].item()), rel=1e-6)
     assert torch.allclose(out["grad_W_s"].float().T, vh["grad_W_s"].float(), rtol=0, atol=1e-2 * vh["grad_W_s"].abs().max().item())
     assert torch.allclose(out["grad_h_s"].float(), vh["grad_h_s"].float(), rtol=0, atol=1e-2 * vh["grad_h_s"].abs().max().item())
 
 
-def test_three_teachers_share_the_backward_products(monkeypatch):
+def test_three_teachers_share_the_backward_products():
     """Three teachers, several vocabulary chunks, no mask, fp32 gradients: every chunk of dL/dz_s is the
     weighted sum over the teachers before the two products run once."""
     import torch
     from oracle import kd_oracle as O
     from paper_2603_01875_amd import kdloss as K
-    monkeypatch.setenv("KD_VOCAB_CHUNK", "512")
     base = I.scaled(I.workload("fkl_bf16"), batch=1, seq=280, H_s=64, V=1800, mask="ones")
     ds = [I.generate(I.scaled(base, H_t=h, seed=500 + i)) for i, h in enumerate((128, 64, 256))]
     weights = (0.5, 0.2, 0.3)
@@ -230,14 +239,15 @@ def test_three_teachers_share_the_backward_products(monkeypatch):
                           I.RKL, 0.5, O.W_VH)
     dev = lambda x: G.to_device(x, I.BF16)
     out = K.kd_loss_fwd_bwd_multi([dev(d["h_t"]) for d in ds], [dev(d["W_t"]) for d in ds], weights,
-                                  dev(h_s), dev(W_s), None, tau=base.tau, kind=I.RKL, grad_dtype=K.F32)
+                                  dev(h_s), dev(W_s), None, tau=base.tau, kind=I.RKL, grad_dtype=K.F32,
+                                  vocab_chunk=512)
     torch.cuda.synchronize()
     G.check(out, ref, "three teachers")
     # one teacher through the multi entry point is the single-teacher call
     one = K.kd_loss_fwd_bwd_multi([dev(ds[0]["h_t"])], [dev(ds[0]["W_t"])], (1.0,), dev(h_s), dev(W_s), None,
-                                  tau=base.tau, kind=I.RKL, grad_dtype=K.F32)
+                                  tau=base.tau, kind=I.RKL, grad_dtype=K.F32, vocab_chunk=512)
     single = K.kd_loss_fwd_bwd(dev(ds[0]["h_t"]), dev(ds[0]["W_t"]), dev(h_s), dev(W_s), None, tau=base.tau,
-                               kind=I.RKL, grad_dtype=K.F32)
+                               kind=I.RKL, grad_dtype=K.F32, vocab_chunk=512)
     torch.cuda.synchronize()
     assert float(one["loss"].item()) == float(single["loss"].item())
     assert torch.equal(one["grad_W_s"], single["grad_W_s"]) and torch.equal(one["grad_h_s"], single["grad_h_s"])
@@ -304,13 +314,12 @@ def test_low_temperature_near_one_hot(kind, beta, tau):
 
 @pytest.mark.parametrize("dtype,H_t,H_s,V", [(I.BF16, 200, 72, 1000), (I.BF16, 128, 64, 1000), (I.F32, 96, 64, 1544),
                                              (I.F32, 128, 128, 1024)])
-def test_hidden_major_heads_off_the_fast_path(dtype, H_t, H_s, V, monkeypatch):
+def test_hidden_major_heads_off_the_fast_path(dtype, H_t, H_s, V):
     """[H,V] heads that cannot be read in place (fp32, or sizes off the 64-element grid) go through the
     transposing re-pack; grad_W_s still comes back as [H_s, V]."""
     import torch
     from oracle import kd_oracle as O
     from paper_2603_01875_amd import kdloss as K
-    monkeypatch.setenv("KD_VOCAB_CHUNK", "512")
     cfg = I.scaled(I.workload("tiny_fkl_f32" if dtype == I.F32 else "rkl_bf16"), batch=2, seq=150, H_t=H_t, H_s=H_s,
                    V=V, mask="tail25")
     data = I.generate(cfg)
@@ -321,7 +330,68 @@ def test_hidden_major_heads_off_the_fast_path(dtype, H_t, H_s, V, monkeypatch):
     dev = lambda x: G.to_device(x, dtype)
     out = K.kd_loss_fwd_bwd(dev(data["h_t"]), dev(hv["W_t"]), dev(data["h_s"]), dev(hv["W_s"]),
                             torch.from_numpy(data["mask"]).cuda(), tau=cfg.tau, kind=cfg.kind, beta=cfg.beta,
-                            w_layout=K.W_HV)
+                            w_layout=K.W_HV, vocab_chunk=512)
     torch.cuda.synchronize()
     assert tuple(out["grad_W_s"].shape) == (H_s, V)
     G.check(out, ref, f"[H,V] heads dtype={dtype} H_t={H_t} H_s={H_s} V={V}")
+
+
+def test_multi_teacher_hidden_major_heads_mixed_sizes():
+    """[H,V] heads with one teacher on the 64-element grid (readable in place) and one off it: the whole
+    call takes the re-packing path, with one student plan (regression: the second teacher used to read a
+    student-head copy that was never made)."""
+    import torch
+    from oracle import kd_oracle as O
+    from paper_2603_01875_amd import kdloss as K
+    base = I.scaled(I.workload("fkl_bf16"), batch=2, seq=150, H_s=128, V=1600)
+    ds = [I.generate(I.scaled(base, H_t=h, seed=640 + i)) for i, h in enumerate((128, 200))]
+    weights = (0.6, 0.4)
+    h_s, W_s, mask = ds[0]["h_s"], ds[0]["W_s"], ds[0]["mask"]
+    hv = lambda W: np.ascontiguousarray(W.T)
+    dev = lambda x: G.to_device(x, I.BF16)
+    for order in ((0, 1), (1, 0)):
+        dd = [ds[i] for i in order]
+        w = [weights[i] for i in order]
+        for kind, beta in ((I.FKL, 0.5), (I.JSD, 0.3)):
+            ref = O.kd_loss_multi([d["h_t"] for d in dd], [hv(d["W_t"]) for d in dd], w, h_s, hv(W_s), mask, base.tau,
+                                  kind, beta, O.W_HV)
+            ref["per_token_loss"] = ref["per_token_loss"] * (mask != 0)
+            out = K.kd_loss_fwd_bwd_multi([dev(d["h_t"]) for d in dd], [dev(hv(d["W_t"])) for d in dd], w, dev(h_s),
+                                          dev(hv(W_s)), torch.from_numpy(mask).cuda(), tau=base.tau, kind=kind,
+                                          beta=beta, w_layout=K.W_HV, vocab_chunk=512)
+            torch.cuda.synchronize()
+            assert tuple(out["grad_W_s"].shape) == (base.H_s, base.V)
+            G.check(out, ref, f"[H,V] two teachers order={order} kind={kind}")
+    # both teachers on the grid: heads read in place
+    ds2 = [I.generate(I.scaled(base, H_t=h, seed=650 + i)) for i, h in enumerate((128, 192))]
+    ref = O.kd_loss_multi([d["h_t"] for d in ds2], [hv(d["W_t"]) for d in ds2], weights, h_s, hv(W_s), mask, base.tau,
+                          I.RKL, 0.5, O.W_HV)
+    ref["per_token_loss"] = ref["per_token_loss"] * (mask != 0)
+    out = K.kd_loss_fwd_bwd_multi([dev(d["h_t"]) for d in ds2], [dev(hv(d["W_t"])) for d in ds2], weights, dev(h_s),
+                                  dev(hv(W_s)), torch.from_numpy(mask).cuda(), tau=base.tau, kind=I.RKL,
+                                  w_layout=K.W_HV, vocab_chunk=512)
+    torch.cuda.synchronize()
+    G.check(out, ref, "[H,V] two teachers in place")
+
+
+def test_sixteen_teachers():
+    """The largest teacher count the call accepts.  Every teacher adds its share to the bf16 staging buffer
+    of dL/dz_s (one rounding per teacher): the gradients must still meet the usual bound."""
+    import torch
+    from oracle import kd_oracle as O
+    from paper_2603_01875_amd import kdloss as K
+    base = I.scaled(I.workload("fkl_bf16"), batch=1, seq=300, H_s=64, V=1288, mask="tail25")
+    ds = [I.generate(I.scaled(base, H_t=64 * (1 + i % 3), w_t_std=(0.02, 0.05)[i % 2], seed=800 + i)) for i in range(16)]
+    rng = np.random.default_rng(16)
+    weights = [float(x) for x in rng.uniform(0.2, 1.0, 16)]
+    h_s, W_s, mask = ds[0]["h_s"], ds[0]["W_s"], ds[0]["mask"]
+    dev = lambda x: G.to_device(x, I.BF16)
+    for kind, beta in ((I.FKL, 0.5), (I.SKEW_RKL, 0.2)):
+        ref = O.kd_loss_multi([d["h_t"] for d in ds], [d["W_t"] for d in ds], weights, h_s, W_s, mask, base.tau,
+                              kind, beta, O.W_VH)
+        ref["per_token_loss"] = ref["per_token_loss"] * (mask != 0)
+        out = K.kd_loss_fwd_bwd_multi([dev(d["h_t"]) for d in ds], [dev(d["W_t"]) for d in ds], weights, dev(h_s),
+                                      dev(W_s), torch.from_numpy(mask).cuda(), tau=base.tau, kind=kind, beta=beta,
+                                      vocab_chunk=512)
+        torch.cuda.synchronize()
+        G.check(out, ref, f"16 teachers kind={kind}")

@@ -24,15 +24,14 @@ def _case(seed):
 
 
 @pytest.mark.parametrize("seed", range(30))
-def test_random_case(seed, monkeypatch):
+def test_random_case(seed):
     cfg, chunk = _case(seed)
-    monkeypatch.setenv("KD_VOCAB_CHUNK", str(chunk))
     data = I.generate(cfg)
     if seed % 7 == 3:                                  # sparse mask: most tokens dropped
         rng = np.random.default_rng(seed)
         data["mask"] = (rng.random(cfg.T) < 0.15).astype(np.uint8)
     extra = G.tvd_tie_allowance(cfg, data) if cfg.kind == I.TVD else None
-    out = G.run_gpu(cfg, data)
+    out = G.run_gpu(cfg, data, vocab_chunk=chunk)
     what = (f"seed={seed} T={cfg.T} H_t={cfg.H_t} H_s={cfg.H_s} V={cfg.V} kind={cfg.kind} tau={cfg.tau:.3f} "
             f"beta={cfg.beta:.2f} dtype={cfg.dtype} mask={cfg.mask} chunk={chunk}")
     G.check(out, G.run_oracle(cfg, data), what, extra)
@@ -56,12 +55,11 @@ def _case_modes(seed):
 
 
 @pytest.mark.parametrize("seed", range(20))
-def test_random_case_other_layout_or_fp8_teacher(seed, monkeypatch):
+def test_random_case_other_layout_or_fp8_teacher(seed):
     import torch
     from oracle import kd_oracle as O
     from paper_2603_01875_amd import kdloss as K
     mode, cfg, chunk = _case_modes(seed)
-    monkeypatch.setenv("KD_VOCAB_CHUNK", str(chunk))
     data = I.generate(cfg)
     what = (f"{mode} seed={seed} T={cfg.T} H_t={cfg.H_t} H_s={cfg.H_s} V={cfg.V} kind={cfg.kind} tau={cfg.tau:.3f} "
             f"beta={cfg.beta:.2f} mask={cfg.mask} chunk={chunk}")
@@ -73,7 +71,7 @@ def test_random_case_other_layout_or_fp8_teacher(seed, monkeypatch):
                                 cfg.beta, O.W_HV)
         ref["per_token_loss"] = ref["per_token_loss"] * (data["mask"] != 0)
         out = K.kd_loss_fwd_bwd(dev(data["h_t"]), dev(hv["W_t"]), dev(data["h_s"]), dev(hv["W_s"]), mask,
-                                tau=cfg.tau, kind=cfg.kind, beta=cfg.beta, w_layout=K.W_HV)
+                                tau=cfg.tau, kind=cfg.kind, beta=cfg.beta, w_layout=K.W_HV, vocab_chunk=chunk)
         d = data
     else:
         f8 = G.fp8_teacher(data)
@@ -81,7 +79,7 @@ def test_random_case_other_layout_or_fp8_teacher(seed, monkeypatch):
         ref = G.run_oracle(cfg, d)
         out = K.kd_loss_fwd_bwd(torch.from_numpy(f8["q_h_t"]).cuda(), torch.from_numpy(f8["q_W_t"]).cuda(),
                                 dev(data["h_s"]), dev(data["W_s"]), mask, tau=cfg.tau, kind=cfg.kind, beta=cfg.beta,
-                                flags=K.FLAG_TEACHER_FP8, teacher_scale=f8["teacher_scale"])
+                                flags=K.FLAG_TEACHER_FP8, teacher_scale=f8["teacher_scale"], vocab_chunk=chunk)
     torch.cuda.synchronize()
     # fp8 MFMA: about 14 bits below the largest product inside one instruction (see test_gpu_fp8.py)
     extra = G.tvd_tie_allowance(cfg, d, rel_gap=3e-4 if mode == "fp8" else 2e-5) if cfg.kind == I.TVD else None
@@ -91,7 +89,7 @@ def test_random_case_other_layout_or_fp8_teacher(seed, monkeypatch):
 
 
 @pytest.mark.parametrize("seed", range(40))
-def test_random_feature_combination(seed, monkeypatch):
+def test_random_feature_combination(seed):
     """Random combinations of the library's options: fp8 teacher, [H,V] heads, fp32 inputs or gradients, one
     to three teachers, temperatures from 0.05 to 20, sparse masks, chunk sizes.  Two documented fp32 limits
     are allowed for: losses below 1e-4 are skipped, and where a divergence saturates (low temperatures) dz
@@ -113,7 +111,7 @@ def test_random_feature_combination(seed, monkeypatch):
                       w_t_std=0.02, w_s_std=float(rng.choice([0.02, 0.06, 0.2])), rms_norm=bool(rng.integers(0, 2)),
                       kind=kind, tau=tau, beta=beta, mask=str(rng.choice(["ones", "tail25", "bernoulli10"])),
                       seed=123000 + seed)
-    monkeypatch.setenv("KD_VOCAB_CHUNK", str(int(rng.choice([256, 1024, 4096, 0]))))
+    chunk = int(rng.choice([256, 1024, 4096, 0]))
     ds = []
     for k in range(nteach):
         H_t = (128 if fp8 else 8) * int(rng.integers(1, 9 if fp8 else 96))
@@ -150,13 +148,14 @@ def test_random_feature_combination(seed, monkeypatch):
             ref["grad_W_s"] = ref["grad_W_s"] + G.to_host(acc0)
         out = K.kd_loss_fwd_bwd(teach[0][2], teach[0][3], dev(data["h_s"]), dev(Ws_o), tm, tau=tau, kind=kind,
                                 beta=beta, w_layout=K.W_HV if hv else K.W_VH, grad_dtype=gdt, flags=flags,
-                                teacher_scale=teach[0][4], grad_W_s=acc0, accumulate_grad_W=acc0 is not None)
+                                teacher_scale=teach[0][4], grad_W_s=acc0, accumulate_grad_W=acc0 is not None,
+                                vocab_chunk=chunk)
     else:
         ref = O.kd_loss_multi([t[0] for t in teach], [t[1] for t in teach], weights, data["h_s"], data["W_s"], mask,
                               tau, kind, beta, O.W_VH)
         out = K.kd_loss_fwd_bwd_multi([t[2] for t in teach], [t[3] for t in teach], weights, dev(data["h_s"]),
                                       dev(data["W_s"]), tm, tau=tau, kind=kind, beta=beta, grad_dtype=gdt, flags=flags,
-                                      teacher_scales=[t[4] for t in teach] if fp8 else None)
+                                      teacher_scales=[t[4] for t in teach] if fp8 else None, vocab_chunk=chunk)
     torch.cuda.synchronize()
     ref["per_token_loss"] = ref["per_token_loss"] * (mask != 0)
     if ref["loss"] < 1e-4 and kind != I.TVD:
