@@ -5,6 +5,9 @@
 #include "kd_launch.h"
 
 #include <cmath>
+#ifdef KD_TRACE_ERRORS
+#include <cstdio>
+#endif
 
 namespace {
 
@@ -202,10 +205,22 @@ struct ProfileScope {
   }
 };
 
-#define KD_TRY(expr)                           \
-  do {                                         \
+// -DKD_TRACE_ERRORS (a debugging build) names the failing call on stderr.
+#ifdef KD_TRACE_ERRORS
+#define KD_TRY(expr)                                                                              \
+  do {                                                                                            \
+    const hipError_t kd_e_ = (expr);                                                              \
+    if (kd_e_ != hipSuccess) {                                                                    \
+      std::fprintf(stderr, "libkdloss: %s:%d: %s -> %s\n", __FILE__, __LINE__, #expr, hipGetErrorString(kd_e_)); \
+      return KD_ERR_LAUNCH;                                                                       \
+    }                                                                                             \
+  } while (0)
+#else
+#define KD_TRY(expr)                                \
+  do {                                              \
     if ((expr) != hipSuccess) return KD_ERR_LAUNCH; \
   } while (0)
+#endif
 
 // Re-pack the operands that need it (fp32 split / K padding / compaction) into the workspace.
 kd_status prepare_operands(const Problem& q, hipStream_t st, bool student, bool teacher) {

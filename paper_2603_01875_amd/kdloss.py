@@ -46,6 +46,11 @@ def lib():
             raise RuntimeError(f"{_LIB_PATH} is missing: build it with "
                                "`python -c 'import __graft_entry__ as g; g.build()'` "
                                "or paper_2603_01875_amd/csrc/build.sh")
+        # The tensors handed to the library and the streams it launches on belong to torch's HIP runtime
+        # (the wheel carries its own copy).  Import torch first, so that this library's HIP calls bind to
+        # that same runtime; loaded before torch it would bring up a second one, which knows neither the
+        # streams nor, on a box that admits one runtime per process, the device.
+        import torch  # noqa: F401
         L = ctypes.CDLL(_LIB_PATH)
         P = ctypes.POINTER(KdLossParams)
         vp = ctypes.c_void_p
