@@ -26,7 +26,8 @@
  *  - plain C ABI; no exceptions, no allocation, no device synchronisation.  The
  *    caller owns every buffer.  The entry points of this header read no
  *    environment variable and keep no state from one call to the next, except
- *    that each kernel's launch attribute is set once per process and device.
+ *    that each kernel's launch attribute is set once per process and device, and
+ *    that kd_loss_fwd_bwd_static works in a device array owned by the library.
  *    (The measurement aids of kdloss_bench.h keep a per-thread hook.)
  *  - all argument checks run on the host before anything touches the GPU, so
  *    they can be exercised on a machine without one.
@@ -53,7 +54,9 @@ typedef enum {
   KD_ERR_PARAM = 4,       /* tau outside [1e-6, 1e6] or not finite, unknown enum, beta outside (0,1) where it is used */
   KD_ERR_WORKSPACE = 5,   /* workspace_bytes smaller than kd_loss_workspace_size */
   KD_ERR_UNSUPPORTED = 6, /* valid request this build does not implement         */
-  KD_ERR_LAUNCH = 7       /* the HIP runtime refused a launch (see hipGetLastError) */
+  KD_ERR_LAUNCH = 7,      /* the HIP runtime refused a launch (see hipGetLastError) */
+  KD_ERR_TOO_LARGE = 8    /* kd_loss_fwd_bwd_static only: the problem needs more scratch memory than
+                             the library's static array holds (KD_STATIC_SCRATCH_BYTES) */
 } kd_status;
 
 /* Sec. 3.4 / Table 1: built-in divergence metrics.
@@ -155,6 +158,29 @@ kd_status kd_loss_fwd_bwd(const kd_loss_params* params,
                           void* grad_h_s, void* grad_W_s,
                           void* workspace, size_t workspace_bytes,
                           void* hip_stream);
+
+/* kd_loss_fwd_bwd for callers that cannot allocate device memory or have no workspace to pass: code
+ * that runs under HIP graph capture, tight serving or training loops, harnesses that forbid hipMalloc.
+ * Same arguments, checks, kernels and results as kd_loss_fwd_bwd, minus the workspace: the scratch memory
+ * is a static device array of KD_STATIC_SCRATCH_BYTES inside the library (each GPU the library runs on
+ * holds its own copy until the process ends).  The call allocates and frees nothing.
+ *  - With params->vocab_chunk == 0 the library picks the widest vocabulary chunk whose plan fits the
+ *    array; with a chunk given, that plan must fit.  A problem that does not fit returns
+ *    KD_ERR_TOO_LARGE and enqueues nothing (the headline workload, T = 4096, H_t = 4096, H_s = 1024,
+ *    V = 151936, fits; T = 32768 with H_s = 4096 does not).
+ *  - The array's address is looked up on the first call on each device (current device = the stream's);
+ *    make that first call outside a graph capture.
+ *  - Nothing in the array has to be zero or survive between calls, but every call on one GPU uses the
+ *    same array: calls that overlap in time on one GPU (two streams, two threads) race.  Serialise them,
+ *    or give the concurrent ones their own workspace through kd_loss_fwd_bwd. */
+#define KD_STATIC_SCRATCH_BYTES ((size_t)128 << 20)
+kd_status kd_loss_fwd_bwd_static(const kd_loss_params* params,
+                                 const void* h_t, const void* W_t,
+                                 const void* h_s, const void* W_s,
+                                 const uint8_t* mask,
+                                 float* loss, float* per_token_loss,
+                                 void* grad_h_s, void* grad_W_s,
+                                 void* hip_stream);
 
 /* Forward only: loss and per-token loss, no gradients (the logit tiles are
  * produced once; twice for JSD).  Same arguments and checks as above. */

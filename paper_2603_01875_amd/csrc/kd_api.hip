@@ -1,13 +1,20 @@
 // C ABI of libkdloss: argument checks, workspace planning and the launch sequence.
 // All checks are host-only and happen before the first HIP call.
+#include <hip/hip_runtime.h>
+
 #include "../../include/kdloss.h"
 #include "../../include/kdloss_bench.h"
 #include "kd_launch.h"
 
+#include <atomic>
 #include <cmath>
 #ifdef KD_TRACE_ERRORS
 #include <cstdio>
 #endif
+
+// Scratch memory of kd_loss_fwd_bwd_static: one array per GPU, owned by the library.  In host code this
+// name is only a handle for hipGetSymbolAddress; the device address is looked up once per device.
+static __device__ __align__(256) unsigned char scratch[KD_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -430,6 +437,54 @@ kd_status kd_loss_fwd_bwd(const kd_loss_params* params, const void* h_t, const v
   return run_backward(&q, 1, st);
 }
 
+kd_status kd_loss_fwd_bwd_static(const kd_loss_params* params, const void* h_t, const void* W_t, const void* h_s,
+                                 const void* W_s, const uint8_t* mask, float* loss, float* per_token_loss,
+                                 void* grad_h_s, void* grad_W_s, void* hip_stream) {
+  kd_status s = check_params(params);
+  if (s != KD_OK) return s;
+  // the plan: the caller's chunk, else the widest one that fits the array
+  kd_loss_params pp = *params;
+  Problem q{};
+  Layout L{};
+  plan(&pp, q, L, true);
+  if (L.total > KD_STATIC_SCRATCH_BYTES && params->vocab_chunk == 0) {
+    for (int vc = 1 << 19; vc >= 256 && L.total > KD_STATIC_SCRATCH_BYTES; vc >>= 1) {
+      if (vc >= q.V_c) continue;
+      pp.vocab_chunk = vc;
+      plan(&pp, q, L, true);
+    }
+  }
+  if (L.total > KD_STATIC_SCRATCH_BYTES) return KD_ERR_TOO_LARGE;
+  // every remaining host-side check, with a stand-in for the scratch address (nothing is dereferenced)
+  q = Problem{};
+  s = check_buffers(&pp, h_t, W_t, h_s, W_s, mask, loss, reinterpret_cast<void*>(uintptr_t{256}),
+                    KD_STATIC_SCRATCH_BYTES, true, grad_h_s, grad_W_s, q, L);
+  if (s != KD_OK) return s;
+  // device address of this GPU's copy of the array, looked up once per device
+  static void* ptr_of_device[64];
+  static std::atomic<uint64_t> have{0};
+  int dev = 0;
+  KD_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) return KD_ERR_UNSUPPORTED;
+  const uint64_t bit = 1ull << dev;
+  if (!(have.load(std::memory_order_acquire) & bit)) {
+    void* ptr = nullptr;
+    KD_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return KD_ERR_LAUNCH;
+    ptr_of_device[dev] = ptr;
+    have.fetch_or(bit, std::memory_order_release);
+  }
+  void* const ptr = ptr_of_device[dev];
+  q = Problem{};
+  s = check_buffers(&pp, h_t, W_t, h_s, W_s, mask, loss, ptr, KD_STATIC_SCRATCH_BYTES, true, grad_h_s, grad_W_s, q, L);
+  if (s != KD_OK) return s;
+  q.per_token_loss = per_token_loss;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  s = run_forward(q, st);
+  if (s != KD_OK) return s;
+  return run_backward(&q, 1, st);
+}
+
 kd_status kd_loss_workspace_size_multi(const kd_loss_params* params, int n_teachers, const int64_t* H_t,
                                        size_t* bytes) {
   if (!bytes || !params || !H_t) return KD_ERR_NULL;
@@ -548,6 +603,7 @@ const char* kd_status_string(kd_status status) {
     case KD_ERR_WORKSPACE: return "workspace too small";
     case KD_ERR_UNSUPPORTED: return "valid request not implemented by this build";
     case KD_ERR_LAUNCH: return "HIP launch failed";
+    case KD_ERR_TOO_LARGE: return "problem needs more scratch memory than the library's static array holds";
   }
   return "unknown status";
 }

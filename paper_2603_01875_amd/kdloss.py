@@ -16,7 +16,8 @@ W_HV, W_VH = 0, 1
 
 KD_OK = 0
 STATUS_NAMES = {0: "KD_OK", 1: "KD_ERR_NULL", 2: "KD_ERR_SHAPE", 3: "KD_ERR_ALIGN", 4: "KD_ERR_PARAM",
-                5: "KD_ERR_WORKSPACE", 6: "KD_ERR_UNSUPPORTED", 7: "KD_ERR_LAUNCH"}
+                5: "KD_ERR_WORKSPACE", 6: "KD_ERR_UNSUPPORTED", 7: "KD_ERR_LAUNCH", 8: "KD_ERR_TOO_LARGE"}
+STATIC_SCRATCH_BYTES = 128 << 20
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "libkdloss.so")
 _lib = None
@@ -60,6 +61,8 @@ def lib():
         L.kd_loss_plan_info.restype = ctypes.c_int
         L.kd_loss_fwd_bwd.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.kd_loss_fwd_bwd.restype = ctypes.c_int
+        L.kd_loss_fwd_bwd_static.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.kd_loss_fwd_bwd_static.restype = ctypes.c_int
         L.kd_loss_fwd.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.kd_loss_fwd.restype = ctypes.c_int
         L.kd_loss_workspace_size_multi.argtypes = [P, ctypes.c_int, ctypes.POINTER(ctypes.c_int64),
@@ -319,6 +322,19 @@ def kd_loss_fwd_bwd_raw(params, h_t, W_t, h_s, W_s, mask, loss, per_token_loss, 
     st = lib().kd_loss_fwd_bwd(ctypes.byref(params), _ptr(h_t), _ptr(W_t), _ptr(h_s), _ptr(W_s), _ptr(mask),
                                _ptr(loss), _ptr(per_token_loss), _ptr(grad_h_s), _ptr(grad_W_s),
                                _ptr(workspace), ctypes.c_size_t(_nbytes(workspace)), ctypes.c_void_p(s))
+    if st != KD_OK:
+        raise KdLossError(st)
+
+
+def kd_loss_fwd_bwd_static_raw(params, h_t, W_t, h_s, W_s, mask, loss, per_token_loss, grad_h_s, grad_W_s,
+                               stream=None):
+    """Thin call of the entry point that needs no workspace (the library's static scratch array)."""
+    import torch
+    _check_raw(params, h_t, W_t, h_s, W_s, mask, loss, per_token_loss, grad_h_s, grad_W_s, None)
+    s = torch.cuda.current_stream().cuda_stream if stream is None else stream
+    st = lib().kd_loss_fwd_bwd_static(ctypes.byref(params), _ptr(h_t), _ptr(W_t), _ptr(h_s), _ptr(W_s), _ptr(mask),
+                                      _ptr(loss), _ptr(per_token_loss), _ptr(grad_h_s), _ptr(grad_W_s),
+                                      ctypes.c_void_p(s))
     if st != KD_OK:
         raise KdLossError(st)
 
