@@ -316,3 +316,34 @@ def test_multi_teacher_gradient_is_gradient_of_weighted_sum():
     b = O.kd_loss_fwd_bwd(teachers[0]["h_t"], teachers[0]["W_t"], h_s, W_s, mask, 1.4, O.FKL, tau2=True)
     assert b["loss"] == pytest.approx(1.96 * a["loss"], rel=1e-14)
     assert np.allclose(b["grad_h_s"], 1.96 * a["grad_h_s"], rtol=1e-13, atol=0)
+
+
+def test_tau2_convention_by_finite_differences_and_high_temperature_limit():
+    """tau2=True: the returned gradients are the derivatives of the returned (tau^2-scaled) loss, and the
+    scaled loss has the textbook high-temperature limit: tau^2 KL(p_t || p_s) -> Var_v(z_t - z_s) / 2
+    (variance over the vocabulary under the uniform distribution), independent of tau."""
+    rng = np.random.default_rng(41)
+    p = _rand_problem(rng, T=3, Ht=6, Hs=5, V=17)
+    mask = np.array([1, 0, 1], dtype=np.uint8)
+    tau = 2.5
+
+    def f(q, kind):
+        return O.kd_loss_fwd_bwd(q["h_t"], q["W_t"], q["h_s"], q["W_s"], mask, tau, kind, 0.3, tau2=True)
+    eps = 1e-6
+    for kind in (O.FKL, O.JSD):
+        r = f(p, kind)
+        for name, grad in (("h_s", r["grad_h_s"]), ("W_s", r["grad_W_s"])):
+            fd = np.zeros_like(p[name])
+            for i in np.ndindex(*p[name].shape):
+                q = {k: v.copy() for k, v in p.items()}
+                q[name][i] += eps; up = f(q, kind)["loss"]
+                q[name][i] -= 2 * eps; dn = f(q, kind)["loss"]
+                fd[i] = (up - dn) / (2 * eps)
+            assert np.abs(fd - grad).max() < 1e-8, (kind, name)
+    z_t = p["h_t"] @ p["W_t"]; z_s = p["h_s"] @ p["W_s"]
+    want = 0.5 * np.var(z_t - z_s, axis=1)
+    for big_tau in (1e3, 1e4):
+        r = O.kd_loss_fwd_bwd(p["h_t"], p["W_t"], p["h_s"], p["W_s"], None, big_tau, O.FKL, tau2=True)
+        assert np.allclose(r["per_token_loss"], want, rtol=5e-3 if big_tau == 1e3 else 5e-4)
+    plain = O.kd_loss_fwd_bwd(p["h_t"], p["W_t"], p["h_s"], p["W_s"], None, 1e3, O.FKL)
+    assert np.all(plain["per_token_loss"] < 1e-5 * want)          # without the factor the loss decays as 1 / tau^2
