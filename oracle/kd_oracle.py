@@ -31,6 +31,14 @@ forward / reverse KL), with `beta` doubling as the skew weight alpha:
   * skewed FKL = KL(p_t || alpha p_t + (1-alpha) p_s),
     skewed RKL = KL(p_s || (1-alpha) p_t + alpha p_s)   (the skew divergences of
     the DistiLLM paper the authors cite; alpha -> 0 recovers FKL / RKL).
+  * AKL (Table 1 lists it; the adaptive KL of the paper by Wu et al. that the authors cite): per token,
+    the vocabulary is split by the teacher: going through the teacher probabilities in descending order,
+    the HEAD is the longest prefix whose cumulative teacher mass stays <= mu (the top entry always belongs
+    to it), the TAIL is the rest; with the gaps g_head = sum_head |p_t - p_s|, g_tail = sum_tail |p_t - p_s|,
+      AKL = g_head / (g_head + g_tail) * FKL + g_tail / (g_head + g_tail) * RKL
+    (weights 1/2, 1/2 when both gaps vanish).  mu is passed in `beta` (the cited method fixes 1/2).
+    The weights are constants for the gradient (the cited method forms them without gradient tracking):
+    g = w_f g_FKL + w_r g_RKL.  The paper itself gives no formula: this is a reading.
 For every divergence that is a function D(p_s) of the student probabilities, the
 gradient through the softmax is g = p_s * (c - sum_v p_s c) with c = dD/dp_s:
   TVD: c = 1/2 sign(p_s - p_t);   skewed FKL: c = -(1-alpha) p_t / M;
@@ -50,8 +58,9 @@ from __future__ import annotations
 
 import numpy as np
 
-FKL, RKL, JSD, TVD, SKEW_FKL, SKEW_RKL = 0, 1, 2, 3, 4, 5
-KIND_NAMES = {FKL: "fkl", RKL: "rkl", JSD: "jsd", TVD: "tvd", SKEW_FKL: "skew_fkl", SKEW_RKL: "skew_rkl"}
+FKL, RKL, JSD, TVD, SKEW_FKL, SKEW_RKL, AKL = 0, 1, 2, 3, 4, 5, 6
+KIND_NAMES = {FKL: "fkl", RKL: "rkl", JSD: "jsd", TVD: "tvd", SKEW_FKL: "skew_fkl", SKEW_RKL: "skew_rkl",
+              AKL: "akl"}
 
 # storage order of an output head: W_HV is the mathematical [H, V] array,
 # W_VH is its transpose [V, H] (the order lm_head.weight is kept in).
@@ -85,6 +94,29 @@ def _xlogy_diff(p, la, lb):
     d = la - lb
     term = np.where(p > 0.0, p * np.where(p > 0.0, d, 0.0), 0.0)
     return term.sum(axis=-1)
+
+
+def akl_head(pt, mu):
+    """Boolean [T,V]: the head of each row of teacher probabilities (see the module header, AKL)."""
+    order = np.argsort(-pt, axis=-1, kind="stable")               # descending teacher probability
+    cum = np.cumsum(np.take_along_axis(pt, order, axis=-1), axis=-1)
+    keep = cum <= mu                                              # prefix whose mass stays within mu
+    keep[..., 0] = True                                           # the top entry is always head
+    head = np.zeros(pt.shape, dtype=bool)
+    np.put_along_axis(head, order, keep, axis=-1)
+    return head
+
+
+def akl_weights(pt, ps, mu):
+    """(w_f, w_r) per row: the shares of the head and tail gaps (AKL)."""
+    head = akl_head(pt, mu)
+    gap = np.abs(pt - ps)
+    g_head = np.where(head, gap, 0.0).sum(axis=-1)
+    g_tail = np.where(head, 0.0, gap).sum(axis=-1)
+    tot = g_head + g_tail
+    safe = np.where(tot > 0.0, tot, 1.0)
+    w_f = np.where(tot > 0.0, g_head / safe, 0.5)
+    return w_f, 1.0 - w_f
 
 
 def divergence_rows(z_t, z_s, tau, kind, beta=0.5):
@@ -129,6 +161,14 @@ def divergence_rows(z_t, z_s, tau, kind, beta=0.5):
             l = _xlogy_diff(ps, ls, lm)
             c = (ls - lm) + 1.0 - alpha * np.exp(ls - lm)
         g = ps * (c - (ps * c).sum(axis=-1, keepdims=True))
+    elif kind == AKL:
+        if not (0.0 < beta < 1.0):
+            raise ValueError("AKL needs 0 < mu < 1")
+        w_f, w_r = akl_weights(pt, ps, beta)
+        l_f = _xlogy_diff(pt, lt, ls)
+        l_r = _xlogy_diff(ps, ls, lt)
+        l = w_f * l_f + w_r * l_r
+        g = w_f[:, None] * (ps - pt) + w_r[:, None] * (ps * ((ls - lt) - l_r[:, None]))
     else:
         raise ValueError("unknown kind")
     return l, g
