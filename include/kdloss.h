@@ -62,8 +62,18 @@ typedef enum {
 /* Sec. 3.4 / Table 1: built-in divergence metrics.
  *   KD_TVD      = 1/2 sum_v |p_t - p_s|
  *   KD_SKEW_FKL = KL(p_t || a p_t + (1-a) p_s),  KD_SKEW_RKL = KL(p_s || (1-a) p_t + a p_s),
- *   with the skew weight a passed in `beta` (0 < a < 1; a -> 0 recovers FKL / RKL). */
-typedef enum { KD_FKL = 0, KD_RKL = 1, KD_JSD = 2, KD_TVD = 3, KD_SKEW_FKL = 4, KD_SKEW_RKL = 5 } kd_kind;
+ *   with the skew weight a passed in `beta` (0 < a < 1; a -> 0 recovers FKL / RKL).
+ *   KD_AKL      = w_f KL(p_t || p_s) + w_r KL(p_s || p_t), the adaptive KL of Table 1 (defined in the paper by
+ *                 Wu et al. that the authors cite, not in the paper itself).  Per token the vocabulary is
+ *                 split by the teacher: in descending order of p_t, the head is the longest prefix whose
+ *                 cumulative teacher mass stays <= mu (the top entry always belongs to it), the tail the
+ *                 rest; w_f = g_head / (g_head + g_tail), w_r = g_tail / (g_head + g_tail) with
+ *                 g = sum |p_t - p_s| over the part (1/2 each if both vanish).  mu is passed in `beta`
+ *                 (0 < mu < 1; the cited method uses 1/2).  The weights are constants for the gradient.
+ *                 The head boundary is found by a search over teacher log-probabilities to within 5e-4
+ *                 (base 2): entries that close to the boundary may fall on either side.  Costs four
+ *                 more passes over the teacher logits and one more over both; not with the fp8 teacher. */
+typedef enum { KD_FKL = 0, KD_RKL = 1, KD_JSD = 2, KD_TVD = 3, KD_SKEW_FKL = 4, KD_SKEW_RKL = 5, KD_AKL = 6 } kd_kind;
 
 typedef enum { KD_BF16 = 0, KD_F32 = 1 } kd_dtype;
 
@@ -101,8 +111,9 @@ typedef struct {
                            are held in fp32: results are meaningful while |z| / tau
                            stays below about 1e5, and a loss far below 1e-4 (very
                            high temperatures) is resolved to about 1e-7 absolute    */
-  float beta;           /* JSD mixing weight on the teacher term, or the skew weight
-                           of the skewed KLs; 0 < beta < 1; ignored for FKL/RKL/TVD */
+  float beta;           /* JSD mixing weight on the teacher term, the skew weight of
+                           the skewed KLs, or AKL's head mass mu; 0 < beta < 1;
+                           ignored for FKL/RKL/TVD                                  */
   int32_t accumulate_grad_W; /* 0: grad_W_s is overwritten. 1: added to (gradient
                            accumulation over micro-batches, Table 3 caption)        */
   int32_t flags;        /* bit set of kd_flags; other bits must be 0                */

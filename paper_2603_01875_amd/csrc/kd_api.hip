@@ -27,7 +27,7 @@ struct Layout {
   size_t meta, rowmap, inv, row_loss, partials, h_sT, dz, gh32;
   size_t prep_h_s, prep_W_s;                       // re-packed student operands (only when needed)
   size_t common;                                   // end of everything above: the same for every teacher
-  size_t rowinfo, prep_h_t, prep_W_t;              // per-teacher block (row statistics, re-packed operands)
+  size_t rowinfo, akl, prep_h_t, prep_W_t;         // per-teacher block (row statistics, re-packed operands)
   size_t total;                                    // end of this teacher's block
 };
 
@@ -39,9 +39,9 @@ kd_status check_params(const kd_loss_params* p) {
   if (p->in_dtype != KD_BF16 && p->in_dtype != KD_F32) return KD_ERR_PARAM;
   if (p->grad_dtype != KD_BF16 && p->grad_dtype != KD_F32) return KD_ERR_PARAM;
   if (p->w_layout != KD_W_HV && p->w_layout != KD_W_VH) return KD_ERR_PARAM;
-  if (p->kind < KD_FKL || p->kind > KD_SKEW_RKL) return KD_ERR_PARAM;
+  if (p->kind < KD_FKL || p->kind > KD_AKL) return KD_ERR_PARAM;
   if (!(p->tau >= 1e-6f && p->tau <= 1e6f)) return KD_ERR_PARAM;   // also rejects NaN
-  if ((p->kind == KD_JSD || p->kind == KD_SKEW_FKL || p->kind == KD_SKEW_RKL) &&
+  if ((p->kind == KD_JSD || p->kind == KD_SKEW_FKL || p->kind == KD_SKEW_RKL || p->kind == KD_AKL) &&
       !(p->beta > 0.f && p->beta < 1.f))
     return KD_ERR_PARAM;
   if (p->accumulate_grad_W != 0 && p->accumulate_grad_W != 1) return KD_ERR_PARAM;
@@ -52,6 +52,7 @@ kd_status check_params(const kd_loss_params* p) {
     if (p->H_t % 128) return KD_ERR_ALIGN;                     // fp8 k-steps are 128 elements
   }
   if (p->w_layout == KD_W_HV && (p->flags & KD_FLAG_TEACHER_FP8)) return KD_ERR_UNSUPPORTED;
+  if (p->kind == KD_AKL && (p->flags & KD_FLAG_TEACHER_FP8)) return KD_ERR_UNSUPPORTED;   // its search pass is bf16 only
   if (p->vocab_chunk != 0 && (p->vocab_chunk < 256 || p->vocab_chunk > (1 << 20) || p->vocab_chunk % 256))
     return KD_ERR_PARAM;
   if (!(std::isfinite(p->loss_scale) && p->loss_scale != 0.f)) return KD_ERR_PARAM;
@@ -138,7 +139,10 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward, si
   L.rowmap = take((size_t)q.T_pad * 4);
   L.inv = take((size_t)q.T * 4);
   L.row_loss = take((size_t)q.T_pad * 4);
-  L.partials = take((size_t)q.n_split * 4 * 5 * q.T_pad * 4);
+  // partial sums per (vocabulary split, quarter of a workgroup, token): 5 statistics, 6 for AKL, whose
+  // search passes keep one sum per threshold
+  const int part_vals = q.kind == KD_AKL ? kd::kAklThresholds : 5;
+  L.partials = take((size_t)q.n_split * 4 * part_vals * q.T_pad * 4);
   L.prep_h_t = L.prep_W_t = L.prep_h_s = L.prep_W_s = 0;
   if (q.prep_hs) L.prep_h_s = take((size_t)q.T * q.K_s * 2);
   if (q.prep_Ws) L.prep_W_s = take((size_t)q.V * q.K_s * 2);
@@ -154,6 +158,7 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward, si
   L.common = off;
   if (teacher_base > off) off = teacher_base;
   L.rowinfo = take((size_t)q.T_pad * 16);
+  L.akl = q.kind == KD_AKL ? take((size_t)q.T_pad * 6 * 4) : 0;
   const size_t t_es = q.t_fp8 ? 1 : 2;
   if (q.prep_ht) L.prep_h_t = take((size_t)q.T * q.K_t * t_es);
   if (q.prep_Wt) L.prep_W_t = take((size_t)q.V * q.K_t * t_es);
@@ -166,6 +171,7 @@ void carve(Problem& q, const Layout& L, void* ws) {
   q.rowmap = reinterpret_cast<int*>(b + L.rowmap);
   q.inv = reinterpret_cast<int*>(b + L.inv);
   q.rowinfo = reinterpret_cast<float*>(b + L.rowinfo);
+  q.akl = q.kind == KD_AKL ? reinterpret_cast<float*>(b + L.akl) : nullptr;
   q.row_loss = reinterpret_cast<float*>(b + L.row_loss);
   q.partials = reinterpret_cast<float*>(b + L.partials);
   q.h_sT = b + L.h_sT;
@@ -258,7 +264,16 @@ kd_status run_forward(const Problem& q, hipStream_t st, bool first_teacher = tru
     KD_TRY(kd::launch_stats(q, st));
   }
   KD_TRY(kd::launch_combine(q, st));
-  if (q.kind >= KD_JSD) {   // divergences that need both log-sum-exps before their row value
+  if (q.kind == KD_AKL) {
+    // the teacher probability that splits each token's vocabulary into head and tail, by a multi-way search
+    // over the teacher logit tiles; then the head and tail gaps, which weigh the two KLs
+    for (int pass = 0; pass < kd::kAklSearchPasses; ++pass) KD_TRY(kd::launch_akl_search(q, st));
+    {
+      ProfileScope ps(KD_PROF_ROWS, st);
+      KD_TRY(kd::launch_rows(q, st));
+    }
+    KD_TRY(kd::launch_akl_weights(q, st));
+  } else if (q.kind >= KD_JSD) {   // divergences that need both log-sum-exps before their row value
     {
       ProfileScope ps(KD_PROF_ROWS, st);
       KD_TRY(kd::launch_rows(q, st));
@@ -403,8 +418,8 @@ kd_status kd_loss_plan_info(const kd_loss_params* params, int64_t* vocab_chunk, 
   // compaction, operand copies (as with a mask), statistics + merge, row pass + merge, loss,
   // h_s^T, per chunk the gradient kernel and the two products, grad_h_s conversion
   if (n_launches)
-    *n_launches = 1 + (q.prep_ht + q.prep_Wt + q.prep_hs + q.prep_Ws) + 2 + (q.kind >= KD_JSD ? 2 : 0) + 1 + 1 +
-                  chunks * 3 + 1;
+    *n_launches = 1 + (q.prep_ht + q.prep_Wt + q.prep_hs + q.prep_Ws) + 2 + (q.kind >= KD_JSD ? 2 : 0) +
+                  (q.kind == KD_AKL ? 2 * kd::kAklSearchPasses : 0) + 1 + 1 + chunks * 3 + 1;
   return KD_OK;
 }
 

@@ -3,7 +3,8 @@
 // Pass structure (one call of kd_loss_fwd_bwd):
 //   stats    : logit tiles (student then teacher) -> online max / sum-exp / cross term per token
 //   combine  : merge partial statistics -> log-sum-exps, FKL / RKL row losses
-//   rows     : (JSD, TVD, skewed KL) logit tiles again -> two row sums per token (RowTerm)
+//   rows     : (JSD, TVD, skewed KL, AKL) logit tiles again -> two row sums per token (RowTerm)
+//   akl search : (AKL) teacher logit tiles only, a few times -> the teacher probability that splits head from tail
 //   finalize : n = sum mask, loss, per-row gradient scale mask/(n tau)
 //   per vocabulary chunk:
 //     grad   : logit tiles again -> dL/dz_s tile in bf16, stored once as [T,Vc]
@@ -80,6 +81,7 @@ struct LogitArgs {
   int T_pad;
   float* partials;     // stats: [n_split*4][5][T_pad];  jsd: [n_split*4][2][T_pad]
   const f32x4* rowinfo;// [T_pad]: {lse2_t, lse2_s, mask/(n tau), row term}
+  const float* akl;    // AKL only: [AKL_ROWS][T_pad] per-token values (see the AKL_* indices)
   bf16_t* dz;          // [T_pad][ldz]   chunk of dL/dz_s, vocabulary contiguous
   int ldz;
   int dz_accumulate;   // add to dz instead of overwriting it (further teachers of a multi-teacher call)
@@ -137,6 +139,31 @@ struct SplitWork {
   __device__ WorkItem item(int i) const { return logit_item<TF8, WHV>(a, a.vt0 + lo + i, tt); }
 };
 
+// The same split of the work, teacher product only (one accumulator): the AKL threshold search.
+template <bool WHV>
+struct TeacherSplitWork {
+  const LogitArgs& a;
+  int tt, split, lo, cnt;
+  __device__ TeacherSplitWork(const LogitArgs& a_) : a(a_) {
+    const int n_tt = meta_get(a.meta, META_N_TT), n_split = meta_get(a.meta, META_N_SPLIT);
+    const int active = n_tt * n_split;
+    tt = split = lo = cnt = 0;
+    if ((int)blockIdx.x >= active) return;
+    const int L = xcd_logical_id(blockIdx.x, active);
+    block_decode(L, n_tt, meta_get(a.meta, META_BA), meta_get(a.meta, META_BB), tt, split);
+    lo = (int)(((int64_t)split * a.n_vt) / n_split);
+    const int hi = (int)(((int64_t)(split + 1) * a.n_vt) / n_split);
+    cnt = hi - lo;
+  }
+  __device__ int n_items() const { return cnt; }
+  __device__ WorkItem item(int i) const {
+    WorkItem it = logit_item<false, WHV>(a, a.vt0 + lo + i, tt);
+    it.A0 = it.A1; it.B0 = it.B1;       // phase 0 is the teacher product
+    it.nk0 = it.nk1;
+    return it;
+  }
+};
+
 // Persistent workgroups striding over the (token tile x vocabulary tile) grid of a chunk.
 template <bool TF8, bool WHV>
 struct ChunkWork {
@@ -167,6 +194,16 @@ constexpr float NEG_BIG = -1.0e30f;   // logit given to vocabulary rows beyond V
 // exponent of a masked entry stays hugely negative instead of cancelling to a rounding residual.
 constexpr float M_FLOOR = -1.0e20f;
 constexpr float LN2 = 0.6931471805599453f;
+
+// Adaptive KL: per-token values kept between its passes, [AKL_ROWS][T_pad] floats.
+enum { AKL_FKL = 0, AKL_RKL = 1,   // the token's forward / reverse KL
+       AKL_LO = 2, AKL_HI = 3,     // search interval of the head threshold (base-2 teacher log-probability):
+                                   // mass{lt >= LO} > mu >= mass{lt >= HI}
+       AKL_LTMAX = 4,              // the largest teacher log-probability of the token
+       AKL_WR = 5,                 // weight of the reverse KL (the forward KL has 1 - that)
+       AKL_ROWS = 6 };
+constexpr int AKL_K = kAklThresholds;   // thresholds tried per search pass: each pass narrows the interval 17-fold
+constexpr float AKL_TOP_EPS = 1.0e-4f;   // entries this close (base-2 log) to the token's largest one count as "the top entry"
 
 __device__ __forceinline__ float fexp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float flog2(float x) { return __builtin_amdgcn_logf(x); }
@@ -204,7 +241,8 @@ __device__ __forceinline__ void mask_tail_rows(const WorkItem& it, AccTile& accS
 //   FKL: X = sum_v 2^(a_t - m_t) (z_t - z_s)      RKL: X = sum_v 2^(a_s - m_s) (z_s - z_t)
 template <int KIND>
 struct StatsEpi {
-  float m_t[NI], S_t[NI], m_s[NI], S_s[NI], X[NI];
+  static constexpr int NV = KIND == 6 ? 6 : 5;     // values per token and part (AKL keeps both cross terms)
+  float m_t[NI], S_t[NI], m_s[NI], S_s[NI], X[NI], X2[NI];
   float c, ts;
   int wm, wn, lane;
   __device__ StatsEpi(float c_, float ts_) : c(c_), ts(ts_) {
@@ -212,7 +250,9 @@ struct StatsEpi {
     wm = (threadIdx.x >> 6) & 1;
     wn = threadIdx.x >> 7;
 #pragma unroll
-    for (int nt = 0; nt < NI; ++nt) { m_t[nt] = M_FLOOR; m_s[nt] = M_FLOOR; S_t[nt] = 0.f; S_s[nt] = 0.f; X[nt] = 0.f; }
+    for (int nt = 0; nt < NI; ++nt) {
+      m_t[nt] = M_FLOOR; m_s[nt] = M_FLOOR; S_t[nt] = 0.f; S_s[nt] = 0.f; X[nt] = 0.f; X2[nt] = 0.f;
+    }
   }
   __device__ void begin_item(const WorkItem&) {}
   __device__ void end_item(const WorkItem& it, AccTile& accS, AccTile& accT) {
@@ -233,7 +273,8 @@ struct StatsEpi {
       const float sct = fexp2(m_t[nt] - nmt);
       const float scs = fexp2(m_s[nt] - nms);
       float st = S_t[nt] * sct, ss = S_s[nt] * scs;
-      float x = X[nt] * (KIND == 0 ? sct : scs);
+      float x = X[nt] * ((KIND == 0 || KIND == 6) ? sct : scs);
+      float x2 = X2[nt] * scs;
 #pragma unroll
       for (int mt = 0; mt < MI; ++mt)
 #pragma unroll
@@ -243,15 +284,16 @@ struct StatsEpi {
           const float es = fexp2(fmaf(zs, c, -nms));
           st += et;
           ss += es;
-          if (KIND == 0) x = fmaf(et, zt - zs, x);
+          if (KIND == 0 || KIND == 6) x = fmaf(et, zt - zs, x);
           if (KIND == 1) x = fmaf(es, zs - zt, x);
+          if (KIND == 6) x2 = fmaf(es, zs - zt, x2);
         }
-      m_t[nt] = nmt; m_s[nt] = nms; S_t[nt] = st; S_s[nt] = ss; X[nt] = x;
+      m_t[nt] = nmt; m_s[nt] = nms; S_t[nt] = st; S_s[nt] = ss; X[nt] = x; X2[nt] = x2;
     }
   }
   __device__ void write(const LogitArgs& a, int tt, int split) const {
     const int part = split * 4 + wm * 2 + (lane >> 5);
-    float* p = a.partials + (int64_t)part * 5 * a.T_pad;
+    float* p = a.partials + (int64_t)part * NV * a.T_pad;
 #pragma unroll
     for (int nt = 0; nt < NI; ++nt) {
       const int t = tt * BN + acc_n(wn, nt, lane);
@@ -260,6 +302,7 @@ struct StatsEpi {
       p[2 * a.T_pad + t] = m_s[nt];
       p[3 * a.T_pad + t] = S_s[nt];
       p[4 * a.T_pad + t] = X[nt];
+      if (KIND == 6) p[5 * a.T_pad + t] = X2[nt];
     }
   }
 };
@@ -320,9 +363,11 @@ struct RowTerm {
   }
 };
 
+// AKL (KIND 6) uses the same pass for its gaps:  a1 = sum over the head of |p_t - p_s|,  a2 = the same over
+// the tail, the head being the entries whose teacher log-probability reaches the token's threshold.
 template <int KIND>
 struct RowsEpi {
-  float A1[NI], A2[NI], Lt[NI], Ls[NI];
+  float A1[NI], A2[NI], Lt[NI], Ls[NI], Thr[NI];
   float c, w, ts;
   int wm, wn, lane;
   __device__ RowsEpi(const LogitArgs& a, int tt) : c(a.c), w(a.beta), ts(a.t_scale) {
@@ -331,8 +376,12 @@ struct RowsEpi {
     wn = threadIdx.x >> 7;
 #pragma unroll
     for (int nt = 0; nt < NI; ++nt) {
-      const f32x4 ri = a.rowinfo[tt * BN + acc_n(wn, nt, lane)];
+      const int t = tt * BN + acc_n(wn, nt, lane);
+      const f32x4 ri = a.rowinfo[t];
       Lt[nt] = ri[0]; Ls[nt] = ri[1]; A1[nt] = 0.f; A2[nt] = 0.f;
+      Thr[nt] = 0.f;
+      if (KIND == 6)    // the top entry is head whatever its mass
+        Thr[nt] = fminf(a.akl[AKL_HI * a.T_pad + t], a.akl[AKL_LTMAX * a.T_pad + t] - AKL_TOP_EPS);
     }
   }
   __device__ void begin_item(const WorkItem&) {}
@@ -348,7 +397,14 @@ struct RowsEpi {
         for (int r = 0; r < 16; ++r) {
           const float lt = fmaf(accT[mt][nt][r], c, -Lt[nt]);
           const float ls = fmaf(accS[mt][nt][r], c, -Ls[nt]);
-          (void)RowTerm<KIND>::template eval<true>(lt, ls, w, a1, a2);
+          if constexpr (KIND == 6) {
+            const float gap = fabsf(fexp2(lt) - fexp2(ls));
+            const bool head = lt >= Thr[nt];
+            a1 += head ? gap : 0.f;
+            a2 += head ? 0.f : gap;
+          } else {
+            (void)RowTerm<KIND>::template eval<true>(lt, ls, w, a1, a2);
+          }
         }
       A1[nt] = a1; A2[nt] = a2;
     }
@@ -369,10 +425,12 @@ struct RowsEpi {
 //   FKL: dz = s (p_s - p_t)
 //   RKL: dz = s p_s (ln2 (l_s - l_t) - R),   R = row loss
 //   JSD, TVD, skewed KL: dz = s p_s (c - R)  (RowTerm above)
+//   AKL: dz = s (w_f (p_s - p_t) + w_r p_s (ln2 (l_s - l_t) - RKL)) = s (p_s (w_r ln2 (l_s - l_t) + R) - w_f p_t),
+//        R = w_f - w_r RKL, the weights being constants for the gradient
 template <int KIND>
 struct GradEpi {
   const LogitArgs& a;
-  float Lt[NI], Ls[NI], sc[NI], R[NI];
+  float Lt[NI], Ls[NI], sc[NI], R[NI], Wr[NI];
   int wm, wn, lane;
   __device__ GradEpi(const LogitArgs& a_) : a(a_) {
     lane = threadIdx.x & 63;
@@ -384,6 +442,8 @@ struct GradEpi {
     for (int nt = 0; nt < NI; ++nt) {
       const f32x4 ri = a.rowinfo[it.n0 + acc_n(wn, nt, lane)];
       Lt[nt] = ri[0]; Ls[nt] = ri[1]; sc[nt] = ri[2]; R[nt] = ri[3];
+      Wr[nt] = 0.f;
+      if (KIND == 6) Wr[nt] = a.akl[AKL_WR * a.T_pad + it.n0 + acc_n(wn, nt, lane)];
     }
   }
   __device__ void end_item(const WorkItem& it, AccTile& accS, AccTile& accT) {
@@ -413,6 +473,8 @@ struct GradEpi {
               g = ps - fexp2(lt);
             } else if (KIND == 1) {
               g = ps * fmaf(LN2, ls - lt, -R[nt]);
+            } else if (KIND == 6) {
+              g = fmaf(ps, fmaf(Wr[nt] * LN2, ls - lt, R[nt]), -(1.f - Wr[nt]) * fexp2(lt));
             } else {
               float u1, u2;
               g = ps * (RowTerm<KIND>::template eval<false>(lt, ls, w, u1, u2) - R[nt]);
@@ -453,6 +515,64 @@ KD_LOGIT_KERNEL void rows_kernel(const LogitArgs a) {
   SplitWork<TF8, WHV> work(a);
   RowsEpi<KIND> epi(a, work.tt);
   tile_loop<2, LCfg, WHV ? 1 : 0, TF8>(work, epi, WHV ? a.V : a.H_s, WHV ? a.V : a.H_t, a.H_s, a.H_t, smem);
+  if (work.cnt > 0) epi.write(a, work.tt, work.split);
+}
+
+// AKL threshold search, one pass: for AKL_K thresholds spread evenly inside the token's current interval
+// (LO, HI), the teacher mass of the entries at or above each threshold.
+struct SearchEpi {
+  float Lt[NI], th0[NI], step[NI];
+  float mass[NI][AKL_K];
+  float c;
+  int wm, wn, lane;
+  __device__ SearchEpi(const LogitArgs& a, int tt) : c(a.c) {
+    lane = threadIdx.x & 63;
+    wm = (threadIdx.x >> 6) & 1;
+    wn = threadIdx.x >> 7;
+#pragma unroll
+    for (int nt = 0; nt < NI; ++nt) {
+      const int t = tt * BN + acc_n(wn, nt, lane);
+      Lt[nt] = a.rowinfo[t][0];
+      const float lo = a.akl[AKL_LO * a.T_pad + t], hi = a.akl[AKL_HI * a.T_pad + t];
+      step[nt] = (hi - lo) * (1.f / (AKL_K + 1));
+      th0[nt] = lo + step[nt];
+#pragma unroll
+      for (int k = 0; k < AKL_K; ++k) mass[nt][k] = 0.f;
+    }
+  }
+  __device__ void begin_item(const WorkItem&) {}
+  __device__ void end_item(const WorkItem& it, AccTile& accT, AccTile&) {
+#pragma unroll
+    for (int nt = 0; nt < NI; ++nt)
+#pragma unroll
+      for (int mt = 0; mt < MI; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const bool ok = acc_m(wm, mt, r, lane) < it.a_rows;      // rows beyond the vocabulary hold nothing
+          const float lt = ok ? fmaf(accT[mt][nt][r], c, -Lt[nt]) : NEG_BIG;
+          const float p = fexp2(lt);
+#pragma unroll
+          for (int k = 0; k < AKL_K; ++k) mass[nt][k] += (lt >= fmaf((float)k, step[nt], th0[nt])) ? p : 0.f;
+        }
+  }
+  __device__ void write(const LogitArgs& a, int tt, int split) const {
+    const int part = split * 4 + wm * 2 + (lane >> 5);
+    float* p = a.partials + (int64_t)part * AKL_K * a.T_pad;
+#pragma unroll
+    for (int nt = 0; nt < NI; ++nt) {
+      const int t = tt * BN + acc_n(wn, nt, lane);
+#pragma unroll
+      for (int k = 0; k < AKL_K; ++k) p[k * a.T_pad + t] = mass[nt][k];
+    }
+  }
+};
+
+template <bool WHV>
+KD_LOGIT_KERNEL void akl_search_kernel(const LogitArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  TeacherSplitWork<WHV> work(a);
+  SearchEpi epi(a, work.tt);
+  tile_loop<1, LCfg, WHV ? 1 : 0, false>(work, epi, WHV ? a.V : a.H_t, WHV ? a.V : a.H_t, a.H_t, a.H_t, smem);
   if (work.cnt > 0) epi.write(a, work.tt, work.split);
 }
 
@@ -636,28 +756,32 @@ __global__ void rowmap_kernel(const uint8_t* mask, int T, int T_pad, int n_split
 // Merge the partial statistics of one (compacted) token; write log-sum-exps and, for FKL / RKL, the
 // row loss.
 __global__ void combine_kernel(const float* partials, const int* meta, int T_pad, int kind, float c,
-                               f32x4* rowinfo, float* row_loss) {
+                               f32x4* rowinfo, float* row_loss, float* akl) {
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= T_pad) return;
   const int n_valid = meta[META_N_VALID], n_parts = 4 * meta[META_N_SPLIT];
+  const int nv = kind == 6 ? 6 : 5;
   if (t >= n_valid) {   // padding rows: probabilities evaluate to 0, gradient scale 0
     rowinfo[t] = f32x4{1.0e30f, 1.0e30f, 0.f, 0.f};
     row_loss[t] = 0.f;
+    if (kind == 6)
+      for (int i = 0; i < AKL_ROWS; ++i) akl[i * T_pad + t] = 0.f;
     return;
   }
   float Mt = M_FLOOR, Ms = M_FLOOR;
   for (int p = 0; p < n_parts; ++p) {
-    const float* q = partials + (int64_t)p * 5 * T_pad + t;
+    const float* q = partials + (int64_t)p * nv * T_pad + t;
     Mt = fmaxf(Mt, q[0]);
     Ms = fmaxf(Ms, q[2 * T_pad]);
   }
-  float St = 0.f, Ss = 0.f, X = 0.f;
+  float St = 0.f, Ss = 0.f, X = 0.f, X2 = 0.f;
   for (int p = 0; p < n_parts; ++p) {
-    const float* q = partials + (int64_t)p * 5 * T_pad + t;
+    const float* q = partials + (int64_t)p * nv * T_pad + t;
     const float wt = fexp2(q[0] - Mt), ws = fexp2(q[2 * T_pad] - Ms);
     St = fmaf(q[1 * T_pad], wt, St);
     Ss = fmaf(q[3 * T_pad], ws, Ss);
-    X = fmaf(q[4 * T_pad], kind == 0 ? wt : ws, X);
+    X = fmaf(q[4 * T_pad], (kind == 0 || kind == 6) ? wt : ws, X);
+    if (kind == 6) X2 = fmaf(q[5 * T_pad], ws, X2);
   }
   // The row loss is a difference of quantities of size log2 V, far larger than itself when the two
   // distributions are close: this last step is done in double (one thread per token, so it costs nothing).
@@ -668,6 +792,61 @@ __global__ void combine_kernel(const float* partials, const int* meta, int T_pad
   const float loss = (float)(0.6931471805599453 * lossd);
   rowinfo[t] = f32x4{(float)Ltd, (float)Lsd, 0.f, loss};
   row_loss[t] = loss;
+  if (kind == 6) {      // both KLs, and the first search interval: from 2^-40 of the largest teacher probability
+    const double fkl = (double)c * X / St - Ltd + Lsd, rkl = (double)c * X2 / Ss - Lsd + Ltd;
+    const float ltmax = (float)((double)Mt - Ltd);
+    akl[AKL_FKL * T_pad + t] = (float)(0.6931471805599453 * fkl);
+    akl[AKL_RKL * T_pad + t] = (float)(0.6931471805599453 * rkl);
+    akl[AKL_LO * T_pad + t] = ltmax - 40.f;
+    akl[AKL_HI * T_pad + t] = ltmax + 1.0e-3f;         // above every entry: mass 0
+    akl[AKL_LTMAX * T_pad + t] = ltmax;
+    akl[AKL_WR * T_pad + t] = 0.f;
+  }
+}
+
+// AKL: merge one search pass.  mass_k = teacher mass at or above threshold k (decreasing in k); the new
+// interval is the pair of neighbouring thresholds between which the mass drops to mu or below.
+__global__ void akl_search_combine_kernel(const float* partials, const int* meta, int T_pad, float mu, float* akl) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  const int n_valid = meta[META_N_VALID], n_parts = 4 * meta[META_N_SPLIT];
+  if (t >= n_valid) return;
+  const float lo = akl[AKL_LO * T_pad + t], hi = akl[AKL_HI * T_pad + t];
+  const float step = (hi - lo) * (1.f / (AKL_K + 1)), th0 = lo + step;
+  float new_lo = lo, new_hi = hi;
+  bool found = false;
+  for (int k = 0; k < AKL_K; ++k) {
+    float m = 0.f;
+    for (int p = 0; p < n_parts; ++p) m += partials[((int64_t)p * AKL_K + k) * T_pad + t];
+    const float th = fmaf((float)k, step, th0);     // the very expression the search kernel compares with
+    if (!found) {
+      if (m <= mu) { new_hi = th; found = true; }
+      else new_lo = th;
+    }
+  }
+  akl[AKL_LO * T_pad + t] = new_lo;
+  akl[AKL_HI * T_pad + t] = new_hi;
+}
+
+// AKL: gaps -> weights, row loss and the row term of the gradient (see GradEpi).
+__global__ void akl_weights_kernel(const float* partials, const int* meta, int T_pad, f32x4* rowinfo,
+                                   float* row_loss, float* akl) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  const int n_valid = meta[META_N_VALID], n_parts = 4 * meta[META_N_SPLIT];
+  if (t >= n_valid) return;
+  float gh = 0.f, gt = 0.f;
+  for (int p = 0; p < n_parts; ++p) {
+    const float* q = partials + (int64_t)p * 2 * T_pad + t;
+    gh += q[0];
+    gt += q[T_pad];
+  }
+  const float tot = gh + gt;
+  const float wr = tot > 0.f ? gt / tot : 0.5f, wf = 1.f - wr;
+  const float fkl = akl[AKL_FKL * T_pad + t], rkl = akl[AKL_RKL * T_pad + t];
+  f32x4 ri = rowinfo[t];
+  ri[3] = wf - wr * rkl;
+  rowinfo[t] = ri;
+  row_loss[t] = wf * fkl + wr * rkl;
+  akl[AKL_WR * T_pad + t] = wr;
 }
 
 // JSD / TVD / skewed KL: merge the row sums into the row loss and R (see RowTerm).
@@ -925,6 +1104,7 @@ static LogitArgs make_logit_args(const Problem& p) {
   a.t_scale = p.t_fp8 ? p.t_scale : 1.f;
   a.T_pad = p.T_pad;
   a.rowinfo = (const f32x4*)p.rowinfo;
+  a.akl = p.akl;
   return a;
 }
 
@@ -940,6 +1120,7 @@ hipError_t launch_stats(const Problem& p, hipStream_t st) {
   switch (p.kind) {
     case 0: return KD_STATS(0);
     case 1: return KD_STATS(1);
+    case 6: return KD_STATS(6);    // both cross terms (AKL)
     default: return KD_STATS(2);   // log-sum-exps only
   }
 #undef KD_STATS
@@ -957,9 +1138,30 @@ hipError_t launch_rows(const Problem& p, hipStream_t st) {
     case 2: return KD_ROWS(2);
     case 3: return KD_ROWS(3);
     case 4: return KD_ROWS(4);
+    case 6: return KD_ROWS(6);
     default: return KD_ROWS(5);
   }
 #undef KD_ROWS
+}
+
+// AKL: one pass of the threshold search (teacher logit tiles only) and its merge.
+hipError_t launch_akl_search(const Problem& p, hipStream_t st) {
+  LogitArgs a = make_logit_args(p);
+  a.vt0 = 0; a.n_vt = p.n_vt;
+  a.partials = p.partials;
+  const int grid = p.n_tt * p.n_split;
+  hipError_t e = p.w_hv_inplace ? launch_big<akl_search_kernel<true>>(grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a)
+                                : launch_big<akl_search_kernel<false>>(grid, LCfg::NT, LCfg::SMEM_BYTES, st, &a);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(akl_search_combine_kernel, dim3((p.T + 255) / 256), dim3(256), 0, st, p.partials, p.meta,
+                     p.T_pad, p.beta, p.akl);
+  return hipGetLastError();
+}
+
+hipError_t launch_akl_weights(const Problem& p, hipStream_t st) {
+  hipLaunchKernelGGL(akl_weights_kernel, dim3((p.T + 255) / 256), dim3(256), 0, st, p.partials, p.meta, p.T_pad,
+                     (f32x4*)p.rowinfo, p.row_loss, p.akl);
+  return hipGetLastError();
 }
 
 hipError_t launch_rowmap(const Problem& p, hipStream_t st) {
@@ -970,7 +1172,7 @@ hipError_t launch_rowmap(const Problem& p, hipStream_t st) {
 
 hipError_t launch_combine(const Problem& p, hipStream_t st) {
   hipLaunchKernelGGL(combine_kernel, dim3((p.T_pad + 255) / 256), dim3(256), 0, st, p.partials, p.meta, p.T_pad,
-                     p.kind, 1.4426950408889634f / p.tau, (f32x4*)p.rowinfo, p.row_loss);
+                     p.kind, 1.4426950408889634f / p.tau, (f32x4*)p.rowinfo, p.row_loss, p.akl);
   return hipGetLastError();
 }
 
@@ -1004,6 +1206,7 @@ hipError_t launch_grad_chunk(const Problem& p, int v0, int width, bool accumulat
     case 2: return KD_GRAD(2);
     case 3: return KD_GRAD(3);
     case 4: return KD_GRAD(4);
+    case 6: return KD_GRAD(6);
     default: return KD_GRAD(5);
   }
 #undef KD_GRAD

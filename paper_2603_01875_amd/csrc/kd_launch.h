@@ -45,6 +45,7 @@ struct Problem {
   int* rowmap;         // [T_pad] compacted index -> token
   int* inv;            // [T] token -> compacted index or -1
   float* rowinfo;      // [T_pad][4]
+  float* akl;          // AKL only: [6][T_pad] per-token values between its passes (null otherwise)
   float* row_loss;     // [T_pad]
   float* partials;     // [n_split*4][5][T_pad]
   void* h_sT;          // bf16 [H_s][T_pad]
@@ -78,6 +79,10 @@ hipError_t launch_quantize_e4m3(const void* src, int src_f32, int64_t n, float i
 hipError_t launch_stats(const Problem& p, hipStream_t st);
 hipError_t launch_combine(const Problem& p, hipStream_t st);
 hipError_t launch_rows(const Problem& p, hipStream_t st);
+hipError_t launch_akl_search(const Problem& p, hipStream_t st);      // one search pass and its merge
+hipError_t launch_akl_weights(const Problem& p, hipStream_t st);
+constexpr int kAklSearchPasses = 4;    // 17-fold narrowing each: 40 -> 4.8e-4 in base-2 log-probability
+constexpr int kAklThresholds = 16;     // per pass (the kernels' AKL_K)
 hipError_t launch_combine_rows(const Problem& p, hipStream_t st);
 hipError_t launch_finalize(const Problem& p, hipStream_t st);
 hipError_t launch_grad_chunk(const Problem& p, int v0, int width, bool accumulate, hipStream_t st);

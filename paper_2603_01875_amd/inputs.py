@@ -17,7 +17,7 @@ from __future__ import annotations
 import dataclasses
 import numpy as np
 
-FKL, RKL, JSD, TVD, SKEW_FKL, SKEW_RKL = 0, 1, 2, 3, 4, 5   # divergence ids (as in the C header)
+FKL, RKL, JSD, TVD, SKEW_FKL, SKEW_RKL, AKL = 0, 1, 2, 3, 4, 5, 6   # divergence ids (as in the C header)
 BF16, F32 = 0, 1                 # storage dtypes
 
 

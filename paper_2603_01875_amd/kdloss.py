@@ -10,7 +10,7 @@ from __future__ import annotations
 import ctypes
 import os
 
-FKL, RKL, JSD, TVD, SKEW_FKL, SKEW_RKL = 0, 1, 2, 3, 4, 5
+FKL, RKL, JSD, TVD, SKEW_FKL, SKEW_RKL, AKL = 0, 1, 2, 3, 4, 5, 6
 BF16, F32 = 0, 1
 W_HV, W_VH = 0, 1
 

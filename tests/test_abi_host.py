@@ -79,6 +79,8 @@ def test_workspace_is_far_below_T_times_V():
     (dict(tau=0.0), 4), (dict(tau=float("nan")), 4), (dict(kind=7), 4),
     (dict(kind=K.JSD, beta=0.0), 4), (dict(kind=K.JSD, beta=1.0), 4), (dict(kind=K.SKEW_FKL, beta=0.0), 4),
     (dict(kind=K.SKEW_RKL, beta=1.5), 4), (dict(kind=-1), 4), (dict(in_dtype=5), 4),
+    (dict(kind=K.AKL, beta=0.0), 4), (dict(kind=K.AKL, beta=1.0), 4),
+    (dict(kind=K.AKL, flags=K.FLAG_TEACHER_FP8, teacher_scale=1.0), 6),
     # [H][V] heads: everything but the fp8 teacher
     (dict(w_layout=K.W_HV, flags=K.FLAG_TEACHER_FP8, teacher_scale=1.0), 6),
     # fp8 teacher: needs a positive finite scale, a bf16 student side and H_t % 128 == 0
@@ -270,3 +272,10 @@ def test_thin_calls_check_sizes_against_the_parameter_block():
     with pytest.raises(ValueError):
         K.kd_loss_fwd_bwd_raw(p, h_t, W_t, h_s, W_s, None, loss, None, torch.zeros(6, 8), torch.zeros(24, 8),
                               torch.zeros(1024, dtype=torch.uint8))
+
+
+def test_akl_needs_room_for_its_search_partials():
+    base = K.kd_loss_workspace_size(_ws(kind=K.FKL))
+    akl = K.kd_loss_workspace_size(_ws(kind=K.AKL))
+    assert base < akl < base + 40 * (1 << 20)            # 16 partial sums per part instead of 5, six floats per token
+    assert K.kd_loss_plan_info(_ws(kind=K.AKL))[1] == K.kd_loss_plan_info(_ws(kind=K.JSD))[1] + 8

@@ -1,0 +1,126 @@
+"""Adaptive KL (AKL) on the GPU against the fp64 oracle.  The head / tail split is a discrete decision per
+vocabulary entry; entries within the library's search resolution of the split are allowed on either side
+(gpu_util.akl_allowance computes, from the oracle's probabilities, how far that can move each output; for
+most rows that is nothing)."""
+import numpy as np
+import pytest
+
+from paper_2603_01875_amd import inputs as I
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(cfg, data, what, **kw):
+    allow = G.akl_allowance(cfg, data)
+    out = G.run_gpu(cfg, data, **kw)
+    ref = G.run_oracle(cfg, data)
+    G.check(out, ref, what, allow)
+    # the allowance must stay a correction, not a loophole: the weight can move by a few percent at most
+    assert allow["max_dw"] < 0.05, f"{what}: allowance {allow['max_dw']}"
+    return out, ref, allow
+
+
+@pytest.mark.parametrize("name,mu", [("fkl_bf16", 0.5), ("rkl_bf16", 0.5), ("long_peaked", 0.5), ("fkl_bf16", 0.2),
+                                     ("rkl_bf16", 0.8)])
+def test_akl_ragged_multi_tile(name, mu):
+    # 3 token tiles (last one ragged, masked tails), 20 vocabulary tiles (last one 8 rows), 5 chunks
+    cfg = I.scaled(I.workload(name), batch=3, seq=200, H_t=192, H_s=128, V=2440, kind=I.AKL, beta=mu)
+    data = I.generate(cfg)
+    out, ref, _ = _run(cfg, data, f"akl {name} mu={mu}", vocab_chunk=512)
+    keep = data["mask"].astype(bool)
+    assert (G.to_host(out["grad_h_s"])[~keep] == 0).all()
+
+
+@pytest.mark.parametrize("tau", [0.5, 2.0])
+def test_akl_temperature_and_large_vocabulary(tau):
+    cfg = I.scaled(I.workload("rkl_bf16"), batch=1, seq=300, H_t=256, H_s=128, V=40008, kind=I.AKL, beta=0.5, tau=tau)
+    data = I.generate(cfg)
+    _run(cfg, data, f"akl tau={tau}")
+
+
+def test_akl_top_entry_heavier_than_mu():
+    """Near one-hot teacher rows: for many tokens the top entry alone exceeds mu and is the whole head."""
+    import torch
+    from oracle import kd_oracle as O
+    cfg = I.scaled(I.workload("long_peaked"), batch=1, seq=256, H_t=1024, H_s=256, V=4096, kind=I.AKL, beta=0.5,
+                   w_t_std=0.15)
+    data = I.generate(cfg)
+    pt = np.exp(O.log_softmax(data["h_t"].astype(np.float64) @ data["W_t"].astype(np.float64).T, cfg.tau))
+    assert (pt.max(axis=1) > 0.5).mean() > 0.1
+    _run(cfg, data, "akl peaked teacher")
+
+
+def test_akl_hidden_major_heads_fp32_inputs_and_forward_only():
+    import torch
+    from oracle import kd_oracle as O
+    from paper_2603_01875_amd import kdloss as K
+    cfg = I.scaled(I.workload("fkl_bf16"), batch=2, seq=150, H_t=128, H_s=64, V=1600, kind=I.AKL, beta=0.5)
+    data = I.generate(cfg)
+    allow = G.akl_allowance(cfg, data)
+    hv = {k: np.ascontiguousarray(data[k].T) for k in ("W_t", "W_s")}
+    ref = O.kd_loss_fwd_bwd(data["h_t"], hv["W_t"], data["h_s"], hv["W_s"], data["mask"], cfg.tau, cfg.kind, cfg.beta,
+                            O.W_HV)
+    ref["per_token_loss"] = ref["per_token_loss"] * (data["mask"] != 0)
+    dev = lambda x: G.to_device(x, I.BF16)
+    mask = torch.from_numpy(data["mask"]).cuda()
+    out = K.kd_loss_fwd_bwd(dev(data["h_t"]), dev(hv["W_t"]), dev(data["h_s"]), dev(hv["W_s"]), mask, tau=cfg.tau,
+                            kind=cfg.kind, beta=cfg.beta, w_layout=K.W_HV, vocab_chunk=512)
+    torch.cuda.synchronize()
+    G.check(out, ref, "akl [H,V] heads", dict(allow, grad_W_s=allow["grad_W_s"].T))
+    # forward only
+    f = K.kd_loss_fwd(dev(data["h_t"]), dev(data["W_t"]), dev(data["h_s"]), dev(data["W_s"]), mask, tau=cfg.tau,
+                      kind=cfg.kind, beta=cfg.beta)
+    full = G.run_gpu(cfg, data)
+    assert torch.equal(f["loss"], full["loss"]) and torch.equal(f["per_token_loss"], full["per_token_loss"])
+    # fp32 inputs (split into bf16 parts inside the library)
+    cfg32 = I.scaled(cfg, dtype=I.F32, H_t=96, H_s=40, V=520)
+    d32 = I.generate(cfg32)
+    G.check(G.run_gpu(cfg32, d32), G.run_oracle(cfg32, d32), "akl fp32", G.akl_allowance(cfg32, d32))
+
+
+def test_akl_two_teachers():
+    import torch
+    from oracle import kd_oracle as O
+    from paper_2603_01875_amd import kdloss as K
+    base = I.scaled(I.workload("fkl_bf16"), batch=2, seq=150, H_s=128, V=1544, kind=I.AKL, beta=0.5)
+    ds = [I.generate(I.scaled(base, H_t=h, w_t_std=sd, seed=300 + i)) for i, (h, sd) in enumerate(((128, 0.02), (192, 0.06)))]
+    weights = (0.3, 0.7)
+    h_s, W_s, mask = ds[0]["h_s"], ds[0]["W_s"], ds[0]["mask"]
+    ref = O.kd_loss_multi([d["h_t"] for d in ds], [d["W_t"] for d in ds], weights, h_s, W_s, mask, base.tau, I.AKL,
+                          0.5, O.W_VH)
+    ref["per_token_loss"] = ref["per_token_loss"] * (mask != 0)
+    allow = None
+    for w, d in zip(weights, ds):
+        a = G.akl_allowance(I.scaled(base, H_t=d["h_t"].shape[1]), dict(d, h_s=h_s, W_s=W_s, mask=mask))
+        allow = ({k: w * v for k, v in a.items()} if allow is None else {k: allow[k] + w * a[k] for k in a})
+    dev = lambda x: G.to_device(x, I.BF16)
+    out = K.kd_loss_fwd_bwd_multi([dev(d["h_t"]) for d in ds], [dev(d["W_t"]) for d in ds], weights, dev(h_s), dev(W_s),
+                                  torch.from_numpy(mask).cuda(), tau=base.tau, kind=I.AKL, beta=0.5, vocab_chunk=512)
+    torch.cuda.synchronize()
+    G.check(out, ref, "akl two teachers", allow)
+
+
+def test_akl_with_fp8_teacher_is_refused():
+    from paper_2603_01875_amd import kdloss as K
+    p = K.make_params(512, 256, 128, 4096, kind=K.AKL, flags=K.FLAG_TEACHER_FP8, teacher_scale=1.0)
+    with pytest.raises(K.KdLossError) as e:
+        K.kd_loss_workspace_size(p)
+    assert e.value.status == 6
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_akl_random_case(seed):
+    rng = np.random.default_rng(41000 + seed)
+    cfg = I.KDConfig(
+        name=f"akl{seed}", batch=int(rng.integers(1, 4)), seq=int(rng.integers(1, 260)),
+        H_t=8 * int(rng.integers(1, 40)), H_s=8 * int(rng.integers(1, 24)), V=8 * int(rng.integers(2, 400)),
+        dtype=I.F32 if seed % 5 == 4 else I.BF16,
+        w_t_std=float(rng.choice([0.02, 0.05, 0.2])), w_s_std=float(rng.choice([0.02, 0.06])),
+        rms_norm=bool(rng.integers(0, 2)), kind=I.AKL, tau=float(np.exp(rng.uniform(np.log(0.3), np.log(5.0)))),
+        beta=float(rng.uniform(0.1, 0.9)), mask=str(rng.choice(["ones", "tail25", "bernoulli10"])), seed=6000 + seed)
+    data = I.generate(cfg)
+    chunk = int(rng.choice([0, 256, 1024]))
+    what = (f"akl seed={seed} T={cfg.T} H_t={cfg.H_t} H_s={cfg.H_s} V={cfg.V} tau={cfg.tau:.3f} mu={cfg.beta:.2f} "
+            f"dtype={cfg.dtype} mask={cfg.mask} chunk={chunk}")
+    _run(cfg, data, what, vocab_chunk=chunk)
