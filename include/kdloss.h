@@ -84,7 +84,8 @@ typedef enum { KD_BF16 = 0, KD_F32 = 1 } kd_dtype;
  * contiguous along the contraction; about 5 % ahead).  KD_W_HV heads are read in place when they are
  * bf16 with H_t, H_s and V multiples of 64; otherwise they are re-packed into the workspace (which then
  * holds copies of both heads) by a slow strided pass, a fallback for small problems.  grad_W_s is written
- * in the caller's order either way.  KD_W_HV with the fp8 teacher returns KD_ERR_UNSUPPORTED. */
+ * in the caller's order either way.  With the fp8 teacher, KD_W_HV heads always take the re-packing path
+ * (better: quantise the frozen head from a [V,H] copy once and pass KD_W_VH). */
 typedef enum { KD_W_HV = 0, KD_W_VH = 1 } kd_wlayout;
 
 /* KD_FLAG_TAU2: multiply the loss, the per-token losses and both gradients by tau^2 (the
@@ -95,7 +96,7 @@ typedef enum { KD_W_HV = 0, KD_W_VH = 1 } kd_wlayout;
  * teacher_scale = scale_h * scale_W.  The teacher logit tiles then run on the fp8 matrix pipe at twice the
  * bf16 rate and half the operand traffic; everything else (student side, divergence, gradients) is unchanged.
  * An extension in the spirit of the paper's FP8 teacher inference (Table 3): the paper does not quantise the
- * head.  Requires in_dtype == KD_BF16, w_layout == KD_W_VH and H_t a multiple of 128.  In the multi-teacher
+ * head.  Requires in_dtype == KD_BF16 and H_t a multiple of 128.  In the multi-teacher
  * call every teacher is then fp8, each with its own scale (teacher_scales[k]; params->teacher_scale is not read). */
 typedef enum { KD_FLAG_TAU2 = 1, KD_FLAG_TEACHER_FP8 = 2 } kd_flags;
 

@@ -51,7 +51,6 @@ kd_status check_params(const kd_loss_params* p) {
     if (p->in_dtype != KD_BF16) return KD_ERR_UNSUPPORTED;     // the student side stays bf16
     if (p->H_t % 128) return KD_ERR_ALIGN;                     // fp8 k-steps are 128 elements
   }
-  if (p->w_layout == KD_W_HV && (p->flags & KD_FLAG_TEACHER_FP8)) return KD_ERR_UNSUPPORTED;
   if (p->kind == KD_AKL && (p->flags & KD_FLAG_TEACHER_FP8)) return KD_ERR_UNSUPPORTED;   // its search pass is bf16 only
   if (p->vocab_chunk != 0 && (p->vocab_chunk < 256 || p->vocab_chunk > (1 << 20) || p->vocab_chunk % 256))
     return KD_ERR_PARAM;
@@ -87,7 +86,9 @@ void plan(const kd_loss_params* p, Problem& q, Layout& L, bool with_backward, si
   // [H][V] heads are read in place as k-major operands when they are bf16 with whole k-steps and a
   // vocabulary that the K-contiguous operand of the grad_h_s product can walk in whole 64-element
   // steps; otherwise both are re-packed (transposing) and the kernels see [V][K] copies
-  q.w_hv_inplace = q.w_hv && !repack_hv && !q.prep_Wt && !q.prep_Ws && q.V % 64 == 0;
+  // (an fp8 teacher head kept as [H][V] bytes is transposed into a [V][H] copy: the fp8 phase of the tile
+  // loop reads K-contiguous rows only)
+  q.w_hv_inplace = q.w_hv && !repack_hv && !q.t_fp8 && !q.prep_Wt && !q.prep_Ws && q.V % 64 == 0;
   if (q.w_hv && !q.w_hv_inplace) q.prep_Wt = q.prep_Ws = 1;
   // hidden states are also re-packed when a mask is given: valid tokens are compacted to the front
   // (the workspace is sized as if it were, since the size query does not see the mask)
@@ -242,7 +243,9 @@ kd_status prepare_operands(const Problem& q, hipStream_t st, bool student, bool 
     KD_TRY(kd::launch_prepare(q.user_h_t, 0, q.T, q.H_t / 2, const_cast<void*>(q.h_t), q.K_t / 2, 2, map, q.meta, 0, st));
   else if (teacher && q.prep_ht)
     KD_TRY(kd::launch_prepare(q.user_h_t, q.in_f32, q.T, q.H_t, const_cast<void*>(q.h_t), q.K_t, 2, map, q.meta, 0, st));
-  if (teacher && q.prep_Wt)
+  if (teacher && q.prep_Wt && q.t_fp8)      // only ever an [H][V] head of e4m3 bytes: transposed copy
+    KD_TRY(kd::launch_transpose(q.user_W_t, q.V, q.H_t, q.V, const_cast<void*>(q.W_t), q.K_t, q.K_t, 1, st));
+  else if (teacher && q.prep_Wt)
     KD_TRY(kd::launch_prepare(q.user_W_t, q.in_f32, q.V, q.H_t, const_cast<void*>(q.W_t), q.K_t, 1, nullptr, q.meta, q.w_hv, st));
   if (student && q.prep_hs)
     KD_TRY(kd::launch_prepare(q.user_h_s, q.in_f32, q.T, q.H_s, const_cast<void*>(q.h_s), q.K_s, 2, map, q.meta, 0, st));
@@ -291,7 +294,7 @@ kd_status run_forward(const Problem& q, hipStream_t st, bool first_teacher = tru
 kd_status run_backward(const Problem* qs, int n_teachers, hipStream_t st) {
   const Problem& q = qs[0];          // everything on the student side is the same for all teachers
   // h_s^T [H_s][T_pad] once (token axis zero-padded): the K-contiguous operand of grad_W_s
-  KD_TRY(kd::launch_transpose(q.h_s, q.K_s, q.T, q.H_s, q.h_sT, q.T_pad, q.T_pad, st));
+  KD_TRY(kd::launch_transpose(q.h_s, q.K_s, q.T, q.H_s, q.h_sT, q.T_pad, q.T_pad, 2, st));
 
   const size_t gsz = q.grad_f32 ? 4 : 2;
   bool first = true;

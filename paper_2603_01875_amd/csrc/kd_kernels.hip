@@ -905,14 +905,14 @@ __global__ void finalize_kernel(const int* meta, const int* inv, const float* ro
 }
 
 // dst[c][r] = src[r][c] for r < R, zero for R <= r < R_pad;  c < C.  64 x 64 tiles through LDS.
-__global__ void transpose_kernel(const bf16_t* src, int64_t ld_src, int R, int C,
-                                 bf16_t* dst, int64_t ld_dst, int R_pad) {
-  __shared__ bf16_t tile[64][66];
+template <class E>
+__global__ void transpose_kernel(const E* src, int64_t ld_src, int R, int C, E* dst, int64_t ld_dst, int R_pad) {
+  __shared__ E tile[64][66];
   const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
   for (int i = ty; i < 64; i += 4) {
     const int r = r0 + i, c = c0 + tx;
-    tile[i][tx] = (r < R && c < C) ? src[(int64_t)r * ld_src + c] : (bf16_t)0.f;
+    tile[i][tx] = (r < R && c < C) ? src[(int64_t)r * ld_src + c] : E(0);
   }
   __syncthreads();
   for (int i = ty; i < 64; i += 4) {
@@ -1213,10 +1213,14 @@ hipError_t launch_grad_chunk(const Problem& p, int v0, int width, bool accumulat
 }
 
 hipError_t launch_transpose(const void* src, int64_t ld_src, int R, int C, void* dst, int64_t ld_dst, int R_pad,
-                            hipStream_t st) {
+                            int elem_bytes, hipStream_t st) {
   dim3 grid((R_pad + 63) / 64, (C + 63) / 64);
-  hipLaunchKernelGGL(transpose_kernel, grid, dim3(256), 0, st, (const bf16_t*)src, ld_src, R, C, (bf16_t*)dst,
-                     ld_dst, R_pad);
+  if (elem_bytes == 1)
+    hipLaunchKernelGGL(transpose_kernel<uint8_t>, grid, dim3(256), 0, st, (const uint8_t*)src, ld_src, R, C,
+                       (uint8_t*)dst, ld_dst, R_pad);
+  else
+    hipLaunchKernelGGL(transpose_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)src, ld_src, R, C,
+                       (bf16_t*)dst, ld_dst, R_pad);
   return hipGetLastError();
 }
 

@@ -86,8 +86,9 @@ constexpr int kAklThresholds = 16;     // per pass (the kernels' AKL_K)
 hipError_t launch_combine_rows(const Problem& p, hipStream_t st);
 hipError_t launch_finalize(const Problem& p, hipStream_t st);
 hipError_t launch_grad_chunk(const Problem& p, int v0, int width, bool accumulate, hipStream_t st);
+// dst[c][r] = src[r][c] (zero for R <= r < R_pad); elements of 1 or 2 bytes
 hipError_t launch_transpose(const void* src, int64_t ld_src, int R, int C, void* dst, int64_t ld_dst, int R_pad,
-                            hipStream_t st);
+                            int elem_bytes, hipStream_t st);
 hipError_t launch_gemm(const GemmDesc& d, int n_cu, hipStream_t st);
 hipError_t launch_gradh_finish(const Problem& p, hipStream_t st);
 // dst bf16 [R][K]: mode 0 = copy, 1 = fp32 split as [hi|hi|lo], 2 = fp32 split as [hi|lo|hi]; zero-padded to K

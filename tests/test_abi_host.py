@@ -81,8 +81,6 @@ def test_workspace_is_far_below_T_times_V():
     (dict(kind=K.SKEW_RKL, beta=1.5), 4), (dict(kind=-1), 4), (dict(in_dtype=5), 4),
     (dict(kind=K.AKL, beta=0.0), 4), (dict(kind=K.AKL, beta=1.0), 4),
     (dict(kind=K.AKL, flags=K.FLAG_TEACHER_FP8, teacher_scale=1.0), 6),
-    # [H][V] heads: everything but the fp8 teacher
-    (dict(w_layout=K.W_HV, flags=K.FLAG_TEACHER_FP8, teacher_scale=1.0), 6),
     # fp8 teacher: needs a positive finite scale, a bf16 student side and H_t % 128 == 0
     (dict(flags=K.FLAG_TEACHER_FP8), 4), (dict(flags=K.FLAG_TEACHER_FP8, teacher_scale=float("inf")), 4),
     (dict(flags=K.FLAG_TEACHER_FP8, teacher_scale=1.0, in_dtype=K.F32), 6),
@@ -279,3 +277,9 @@ def test_akl_needs_room_for_its_search_partials():
     akl = K.kd_loss_workspace_size(_ws(kind=K.AKL))
     assert base < akl < base + 40 * (1 << 20)            # 16 partial sums per part instead of 5, six floats per token
     assert K.kd_loss_plan_info(_ws(kind=K.AKL))[1] == K.kd_loss_plan_info(_ws(kind=K.JSD))[1] + 8
+
+
+def test_hidden_major_heads_with_fp8_teacher_are_repacked():
+    vh = K.kd_loss_workspace_size(_ws(flags=K.FLAG_TEACHER_FP8, teacher_scale=1.0))
+    hv = K.kd_loss_workspace_size(_ws(flags=K.FLAG_TEACHER_FP8, teacher_scale=1.0, w_layout=K.W_HV))
+    assert hv >= vh + 151936 * (4096 + 2 * 1024)        # a byte copy of the teacher head, a bf16 one of the student's

@@ -150,3 +150,26 @@ def test_two_fp8_teachers_with_their_own_scales():
                                       vocab_chunk=512)
         torch.cuda.synchronize()
         G.check(out, ref, f"two fp8 teachers kind={kind}")
+
+
+def test_fp8_teacher_with_hidden_major_heads():
+    """[H,V] heads with the fp8 teacher: the e4m3 head is transposed into a [V,H] copy inside the library;
+    grad_W_s comes back as [H_s, V]."""
+    import torch
+    from oracle import kd_oracle as O
+    from paper_2603_01875_amd import kdloss as K
+    cfg = I.scaled(I.workload("rkl_bf16"), batch=2, seq=150, H_t=256, H_s=128, V=1608)
+    data = I.generate(cfg)
+    f8 = G.fp8_teacher(data)
+    hv = lambda W: np.ascontiguousarray(W.T)
+    ref = O.kd_loss_fwd_bwd(f8["h_t"], hv(f8["W_t"]), data["h_s"], hv(data["W_s"]), data["mask"], cfg.tau, cfg.kind,
+                            cfg.beta, O.W_HV)
+    ref["per_token_loss"] = ref["per_token_loss"] * (data["mask"] != 0)
+    out = K.kd_loss_fwd_bwd(torch.from_numpy(f8["q_h_t"]).cuda(), torch.from_numpy(hv(f8["q_W_t"])).cuda(),
+                            G.to_device(data["h_s"], I.BF16), G.to_device(hv(data["W_s"]), I.BF16),
+                            torch.from_numpy(data["mask"]).cuda(), tau=cfg.tau, kind=cfg.kind, beta=cfg.beta,
+                            w_layout=K.W_HV, flags=K.FLAG_TEACHER_FP8, teacher_scale=f8["teacher_scale"],
+                            vocab_chunk=512)
+    torch.cuda.synchronize()
+    assert tuple(out["grad_W_s"].shape) == (cfg.H_s, cfg.V)
+    G.check(out, ref, "fp8 teacher, [H,V] heads")
