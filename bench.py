@@ -308,7 +308,12 @@ def main():
         "kernel_ms": dict(stats=stats_avg, **fam),
         "workspace_bytes": int(ws.numel()), "two_T_V_bytes": 2 * T * V,
         "loss": float(loss.item()),
+        "library": {"path": os.path.relpath(K._LIB_PATH, ROOT), "build": K.lib().kd_build_info().decode(),
+                    "ablation": K.lib().kd_build_ablation()},
     }
+    if out["library"]["ablation"]:
+        out["data"] = "synthetic; ABLATION BUILD %d: a measurement build, its results are wrong by design" % \
+            out["library"]["ablation"]
     # free the headline problem before the other workloads (the largest needs about 8 GB)
     del dev, gW, gh, ws
     torch.cuda.empty_cache()

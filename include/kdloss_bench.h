@@ -44,6 +44,12 @@ kd_status kd_loss_profile_clock(void* two_int64_device);
  * bf16 values; the shader clock under this load depends on them, so pass values like real data).
  * Executes KD_PROBE_FLOP_PER_ITER * iters flop.  `sink` (device, 256 * 512 floats) receives sums that
  * only keep the work alive.  Time the launch with events on `hip_stream`. */
+/* Compile-time configuration of the loaded library as text (tile shapes, ablation switch), and the ablation
+ * switch alone: 0 for the product; anything else is a measurement build (-DKD_ABLATE=n, see the top of
+ * kd_kernels.hip) whose results are wrong by design. */
+const char* kd_build_info(void);
+int kd_build_ablation(void);
+
 #define KD_PROBE_FLOP_PER_ITER (256.0 * 8 * 8 * 2 * 32 * 32 * 16)
 kd_status kd_probe_mfma_rate(const void* operands, int iters, float* sink, void* hip_stream);
 

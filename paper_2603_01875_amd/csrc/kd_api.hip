@@ -611,6 +611,9 @@ kd_status kd_loss_profile_hook(int which, void** events, int n_events) {
 
 int kd_loss_profile_count(void) { return g_hook.used; }
 
+const char* kd_build_info(void) { return kd::build_info(); }
+int kd_build_ablation(void) { return kd::build_ablation(); }
+
 const char* kd_status_string(kd_status status) {
   switch (status) {
     case KD_OK: return "ok";

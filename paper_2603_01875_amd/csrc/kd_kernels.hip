@@ -27,6 +27,16 @@
                                         // bursts of transposing LDS reads of the k-major operand)
 #endif
 
+// Ablation builds for measurements (never the product: RESULTS ARE WRONG when this is not 0).  They take one
+// cost out of the logit kernels so that its share of the time and of the shader clock can be read off:
+//   1  every workgroup loads the same head rows and the same token rows (all loads hit the L2: no traffic
+//      behind it), everything else unchanged
+//   2  the statistics epilogue (two exp2 per logit pair, running maxima) is replaced by a plain sum
+//   3  both
+#ifndef KD_ABLATE
+#define KD_ABLATE 0
+#endif
+
 namespace kd {
 
 typedef TileCfg<KD_LOGIT_CFG> LCfg;   // logit tiles: two accumulators per tile
@@ -108,6 +118,12 @@ __device__ __forceinline__ WorkItem logit_item(const LogitArgs& a, int vt, int t
     it.A1 = a.W_t + (int64_t)vt * BM * a.H_t;
     it.B1 = a.h_t + (int64_t)tt * BN * a.H_t;
   }
+#if KD_ABLATE & 1
+  {   // same operand rows for every tile (the tile's coordinates below stay its own)
+    it.B0 = a.h_s; it.B1 = a.h_t;
+    it.A0 = a.W_s; it.A1 = a.W_t;
+  }
+#endif
   it.ka_rows = it.kb_rows = 1 << 30;       // hidden sizes are whole k-steps: no k-row is ever missing
   it.a_rows = min(BM, a.V - vt * BM);
   it.b_rows = min(BN, a.T - tt * BN);
@@ -256,6 +272,15 @@ struct StatsEpi {
   }
   __device__ void begin_item(const WorkItem&) {}
   __device__ void end_item(const WorkItem& it, AccTile& accS, AccTile& accT) {
+#if KD_ABLATE & 2
+#pragma unroll
+    for (int nt = 0; nt < NI; ++nt)
+#pragma unroll
+      for (int mt = 0; mt < MI; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { S_t[nt] += accT[mt][nt][r]; S_s[nt] += accS[mt][nt][r]; }
+    return;
+#endif
     scale_teacher(accT, ts);
     mask_tail_rows(it, accS, accT, wm, lane);
 #pragma unroll
@@ -1277,6 +1302,14 @@ hipError_t launch_quantize_e4m3(const void* src, int src_f32, int64_t n, float i
                      inv_scale, (uint8_t*)dst);
   return hipGetLastError();
 }
+
+#define KD_STR2(...) #__VA_ARGS__
+#define KD_STR(...) KD_STR2(__VA_ARGS__)
+const char* build_info() {
+  return "logit tile cfg (MI,NI,WN,BK,NST) = " KD_STR(KD_LOGIT_CFG) "; product tile cfg = " KD_STR(KD_GEMM_CFG)
+         "; ablation = " KD_STR(KD_ABLATE);
+}
+int build_ablation() { return KD_ABLATE; }
 
 hipError_t launch_gradh_finish(const Problem& p, hipStream_t st) {
   const int64_t n = (int64_t)p.T * p.H_s;

@@ -91,6 +91,8 @@ hipError_t launch_transpose(const void* src, int64_t ld_src, int R, int C, void*
                             int elem_bytes, hipStream_t st);
 hipError_t launch_gemm(const GemmDesc& d, int n_cu, hipStream_t st);
 hipError_t launch_gradh_finish(const Problem& p, hipStream_t st);
+const char* build_info();     // compile-time configuration of the kernels (tile shapes, ablation switch)
+int build_ablation();
 // dst bf16 [R][K]: mode 0 = copy, 1 = fp32 split as [hi|hi|lo], 2 = fp32 split as [hi|lo|hi]; zero-padded to K
 hipError_t launch_prepare(const void* src, int src_f32, int R, int H, void* dst, int K, int split_mode,
                           const int* rowmap, const int* meta, int src_transposed, hipStream_t st);

@@ -19,7 +19,10 @@ STATUS_NAMES = {0: "KD_OK", 1: "KD_ERR_NULL", 2: "KD_ERR_SHAPE", 3: "KD_ERR_ALIG
                 5: "KD_ERR_WORKSPACE", 6: "KD_ERR_UNSUPPORTED", 7: "KD_ERR_LAUNCH", 8: "KD_ERR_TOO_LARGE"}
 STATIC_SCRATCH_BYTES = 128 << 20
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "libkdloss.so")
+# KDLOSS_LIBRARY names another build of the library (measurement builds for the profiles); default: the
+# product build next to the sources
+_LIB_PATH = os.environ.get("KDLOSS_LIBRARY") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc",
+                                                             "libkdloss.so")
 _lib = None
 
 
@@ -83,6 +86,10 @@ def lib():
         L.kd_loss_profile_hook.restype = ctypes.c_int
         L.kd_loss_profile_count.argtypes = []
         L.kd_loss_profile_count.restype = ctypes.c_int
+        L.kd_build_info.argtypes = []
+        L.kd_build_info.restype = ctypes.c_char_p
+        L.kd_build_ablation.argtypes = []
+        L.kd_build_ablation.restype = ctypes.c_int
         L.kd_status_string.argtypes = [ctypes.c_int]
         L.kd_status_string.restype = ctypes.c_char_p
         _lib = L
