@@ -37,6 +37,10 @@
 #define KD_ABLATE 0
 #endif
 
+#if KD_LOOP_ABLATE
+#error "KD_LOOP_ABLATE is for tile_loop_bench.hip only: the library's kernels must compute their products"
+#endif
+
 namespace kd {
 
 typedef TileCfg<KD_LOGIT_CFG> LCfg;   // logit tiles: two accumulators per tile

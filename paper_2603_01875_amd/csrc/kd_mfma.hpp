@@ -16,6 +16,13 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+// Loop ablations for measurements with tile_loop_bench.hip only (the library is never built with them: the
+// products come out wrong).  Bit 1: no global->LDS loads after the first k-steps; bit 2: no LDS fragment reads
+// after the first; bit 4: no workgroup barrier.  Each takes one consumer of time and energy out of the loop.
+#ifndef KD_LOOP_ABLATE
+#define KD_LOOP_ABLATE 0
+#endif
+
 namespace kd {
 
 typedef __bf16 bf16_t;
@@ -304,7 +311,9 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
   set_cursor();
 
   // loads [j0, j1) of the k-step under the cursor, into LDS stage `stage`
+  bool in_main_loop = false;     // (only read by the loop ablations)
   auto issue_loads = [&](int stage, int j0, int j1) {
+    if ((KD_LOOP_ABLATE & 1) && in_main_loop && (l_item > 0 || l_k > 5)) return;   // every stage holds data by then
     char* sbase = smem + stage * STAGE_BYTES + wave * 1024;
 #pragma unroll
     for (int j = j0; j < j1; ++j)
@@ -384,6 +393,7 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
 
   auto read_frags = [&](int st, auto ks_c, AFrag (&af)[MI], BFrag (&bfr)[NI]) {
     constexpr int ks = decltype(ks_c)::value;
+    if ((KD_LOOP_ABLATE & 2) && in_main_loop) return;
     const char* base = smem + st * STAGE_BYTES;
     const uint32_t lbase = lds0 + st * STAGE_BYTES;
 #pragma unroll
@@ -514,7 +524,8 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
       schedule_substep();
     });
     // k-step g+1 must have landed; after the barrier nobody reads stage `stage` any more
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(Cfg::WAIT_STEADY) : "memory");
+    if (KD_LOOP_ABLATE & 4) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(Cfg::WAIT_STEADY) : "memory");
+    else asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(Cfg::WAIT_STEADY) : "memory");
     // last sub-step (KS-1, odd): multiplies (fa1, fb1), fetches sub-step 0 of the next k-step
     wait_frags(fa1, fb1);
     issue_loads(fill, Cfg::LOADS_BEFORE_BARRIER, LOADS);
@@ -535,6 +546,7 @@ __device__ __forceinline__ void tile_loop(const Work& work, Epi& epi,
   }
   asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(Cfg::WAIT_PROLOGUE) : "memory");
   read_frags(0, IntC<0>{}, fa0, fb0);
+  in_main_loop = true;
 
   for (int c_item = 0; c_item < n_items; ++c_item) {
     const WorkItem ci = work.item(c_item);

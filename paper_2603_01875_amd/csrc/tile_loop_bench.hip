@@ -7,6 +7,8 @@
 //         -DCFG="4,2,4,32,4" tile_loop_bench.hip -o tile_loop_bench_256x256 && ./tile_loop_bench_256x256 153600 4096 4096
 //
 // CFG = MI, NI, WN, BK, NST (see TileCfg): tile = 64 MI x 256, 2 x WN waves, NST stages of BK elements.
+// -DKD_LOOP_ABLATE=n (bit 1: no global->LDS loads, 2: no LDS fragment reads, 4: no barrier; see kd_mfma.hpp)
+// takes one consumer out of the loop: what is left runs that much faster.
 // Operands are N(0,1) and N(0,0.02^2) values rounded to bf16, drawn on the device (the shader clock the chip
 // holds under MFMA load depends on the operand values).  The result is reduced to one number per lane and stored
 // only if it matches a value it cannot have: nothing is written, nothing is checked here.
@@ -116,7 +118,7 @@ int main(int argc, char** argv) {
   float ms = 0.f;
   HIP_OK(hipEventElapsedTime(&ms, e0, e1));
   ms /= reps;
-  printf("tile cfg (MI,NI,WN,BK,NST) = %s: tile %d x %d, %d waves, %d KB LDS | M=%d N=%d K=%d: %.3f ms, %.0f TFLOP/s\n", STR(CFG),
+  printf("loop ablation %d, tile cfg (MI,NI,WN,BK,NST) = %s: tile %d x %d, %d waves, %d KB LDS | M=%d N=%d K=%d: %.3f ms, %.0f TFLOP/s\n", KD_LOOP_ABLATE, STR(CFG),
          Cfg::BM, BN, Cfg::NT / 64, Cfg::SMEM_BYTES / 1024, M, N, K, ms, 2.0 * M * N * K / ms / 1e9);
   return 0;
 }
