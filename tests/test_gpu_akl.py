@@ -124,3 +124,25 @@ def test_akl_random_case(seed):
     what = (f"akl seed={seed} T={cfg.T} H_t={cfg.H_t} H_s={cfg.H_s} V={cfg.V} tau={cfg.tau:.3f} mu={cfg.beta:.2f} "
             f"dtype={cfg.dtype} mask={cfg.mask} chunk={chunk}")
     _run(cfg, data, what, vocab_chunk=chunk)
+
+
+def test_akl_all_tokens_masked_and_no_workspace_entry_point():
+    import torch
+    from paper_2603_01875_amd import kdloss as K
+    cfg = I.scaled(I.workload("fkl_bf16"), batch=1, seq=300, H_t=128, H_s=64, V=776, kind=I.AKL, beta=0.5)
+    data = I.generate(cfg)
+    z = G.run_gpu(cfg, dict(data, mask=np.zeros(cfg.T, np.uint8)))
+    assert float(z["loss"].item()) == 0.0
+    assert not z["grad_h_s"].any() and not z["grad_W_s"].any() and not z["per_token_loss"].any()
+    # the entry point that works in the library's static scratch array gives the same bits
+    d = {k: G.to_device(data[k], cfg.dtype) for k in ("h_t", "W_t", "h_s", "W_s")}
+    mask = torch.from_numpy(data["mask"]).cuda()
+    p = K.make_params(cfg.T, cfg.H_t, cfg.H_s, cfg.V, cfg.kind, cfg.tau, cfg.beta)
+    a = G.run_gpu(cfg, data)
+    loss = torch.empty(1, device="cuda"); ptl = torch.empty(cfg.T, device="cuda")
+    gh = torch.empty(cfg.T, cfg.H_s, device="cuda", dtype=torch.bfloat16)
+    gW = torch.empty(cfg.V, cfg.H_s, device="cuda", dtype=torch.bfloat16)
+    K.kd_loss_fwd_bwd_static_raw(p, d["h_t"], d["W_t"], d["h_s"], d["W_s"], mask, loss, ptl, gh, gW)
+    torch.cuda.synchronize()
+    assert torch.equal(loss, a["loss"]) and torch.equal(ptl, a["per_token_loss"])
+    assert torch.equal(gh, a["grad_h_s"]) and torch.equal(gW, a["grad_W_s"])
