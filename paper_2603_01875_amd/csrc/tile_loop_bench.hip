@@ -28,7 +28,7 @@
 using namespace kd;
 typedef TileCfg<CFG> Cfg;
 
-struct Args { const bf16_t* A; const bf16_t* B; float* out; int K, n_mt, n_nt; };
+struct Args { const bf16_t* A; const bf16_t* B; float* out; long long* clocks; int K, n_mt, n_nt; };
 
 // 8 x 4 blocks of tiles per XCD (the map of the library's backward products)
 struct Work {
@@ -73,7 +73,12 @@ __global__ __launch_bounds__(Cfg::NT, 1) void product_kernel(const Args a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   Work w(a);
   SumEpi e(a);
+  const long long c0 = clock64(), r0 = wall_clock64();
   tile_loop<1, Cfg>(w, e, a.K, a.K, a.K, a.K, smem);
+  if (blockIdx.x == 0 && threadIdx.x == 0) {     // shader cycles and 100 MHz ticks of workgroup 0's loop
+    a.clocks[0] = clock64() - c0;
+    a.clocks[1] = wall_clock64() - r0;
+  }
 }
 
 // x[i] = bf16(std * N(0,1)), from a counter-based hash and the Box-Muller transform
@@ -98,12 +103,14 @@ int main(int argc, char** argv) {
   }
   bf16_t *A, *B;
   float* out;
+  long long* clocks;
   const size_t na = (size_t)M * K, nb = (size_t)N * K;
   HIP_OK(hipMalloc(&A, na * 2)); HIP_OK(hipMalloc(&B, nb * 2)); HIP_OK(hipMalloc(&out, 4096));
+  HIP_OK(hipMalloc(&clocks, 16));
   hipLaunchKernelGGL(fill_normal, dim3((unsigned)((na + 255) / 256)), dim3(256), 0, 0, A, na, 0.02f, 1u);
   hipLaunchKernelGGL(fill_normal, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, 0, B, nb, 1.0f, 2u);
   HIP_OK(hipDeviceSynchronize());
-  Args a{A, B, out, K, M / Cfg::BM, N / BN};
+  Args a{A, B, out, clocks, K, M / Cfg::BM, N / BN};
   HIP_OK(hipFuncSetAttribute((const void*)product_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::SMEM_BYTES));
   hipEvent_t e0, e1;
   HIP_OK(hipEventCreate(&e0)); HIP_OK(hipEventCreate(&e1));
@@ -118,7 +125,12 @@ int main(int argc, char** argv) {
   float ms = 0.f;
   HIP_OK(hipEventElapsedTime(&ms, e0, e1));
   ms /= reps;
-  printf("loop ablation %d, tile cfg (MI,NI,WN,BK,NST) = %s: tile %d x %d, %d waves, %d KB LDS | M=%d N=%d K=%d: %.3f ms, %.0f TFLOP/s\n", KD_LOOP_ABLATE, STR(CFG),
-         Cfg::BM, BN, Cfg::NT / 64, Cfg::SMEM_BYTES / 1024, M, N, K, ms, 2.0 * M * N * K / ms / 1e9);
+  long long hc[2] = {0, 1};
+  HIP_OK(hipMemcpy(hc, clocks, 16, hipMemcpyDeviceToHost));
+  const double ghz = (double)hc[0] / (double)hc[1] * 0.1;
+  const double tflops = 2.0 * M * N * K / ms / 1e9;
+  printf("loop ablation %d, tile cfg (MI,NI,WN,BK,NST) = %s: tile %d x %d, %d waves, %d KB LDS | M=%d N=%d K=%d: %.3f ms, %.0f TFLOP/s, shader clock %.2f GHz, MFMA busy %.2f\n",
+         KD_LOOP_ABLATE, STR(CFG), Cfg::BM, BN, Cfg::NT / 64, Cfg::SMEM_BYTES / 1024, M, N, K, ms, tflops, ghz,
+         tflops / (1024 * 1024 * ghz * 1e9 / 1e12));
   return 0;
 }
