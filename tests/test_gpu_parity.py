@@ -395,3 +395,37 @@ def test_sixteen_teachers():
                                       vocab_chunk=512)
         torch.cuda.synchronize()
         G.check(out, ref, f"16 teachers kind={kind}")
+
+
+@pytest.mark.parametrize("kind,beta,T,V,chunk", [(I.FKL, 0.5, 300, 1288, 512), (I.JSD, 0.3, 257, 2440, 0),
+                                                 (I.AKL, 0.5, 130, 1000, 256), (I.TVD, 0.5, 700, 40008, 0)])
+def test_guard_bands_around_outputs_and_workspace_stay_intact(kind, beta, T, V, chunk):
+    """Every output and the workspace are carved out of one buffer with 4 KiB guard bands between them (ragged
+    sizes, so the tails of tiles and chunks lie next to a band); the call must write inside its buffers only."""
+    import torch
+    from paper_2603_01875_amd import kdloss as K
+    cfg = I.scaled(I.workload("fkl_bf16"), batch=1, seq=T, H_t=192, H_s=72, V=V, kind=kind, beta=beta)
+    data = I.generate(cfg)
+    d = {k: G.to_device(data[k], cfg.dtype) for k in ("h_t", "W_t", "h_s", "W_s")}
+    mask = torch.from_numpy(data["mask"]).cuda()
+    p = K.make_params(cfg.T, cfg.H_t, cfg.H_s, cfg.V, kind, cfg.tau, beta, vocab_chunk=chunk)
+    sizes = dict(loss=4, ptl=4 * cfg.T, gh=2 * cfg.T * cfg.H_s, gW=2 * cfg.V * cfg.H_s, ws=K.kd_loss_workspace_size(p))
+    GUARD = 4096
+    offs, off = {}, GUARD
+    for k, n in sizes.items():
+        offs[k] = off
+        off = (off + n + GUARD + 255) // 256 * 256
+    buf = torch.full((off + GUARD,), 0xA5, dtype=torch.uint8, device="cuda")
+    view = lambda k, dt: buf[offs[k]:offs[k] + sizes[k]].view(dt)
+    loss, ptl = view("loss", torch.float32), view("ptl", torch.float32)
+    gh = view("gh", torch.bfloat16).view(cfg.T, cfg.H_s)
+    gW = view("gW", torch.bfloat16).view(cfg.V, cfg.H_s)
+    ws = view("ws", torch.uint8)
+    K.kd_loss_fwd_bwd_raw(p, d["h_t"], d["W_t"], d["h_s"], d["W_s"], mask, loss, ptl, gh, gW, ws)
+    torch.cuda.synchronize()
+    inside = torch.zeros_like(buf, dtype=torch.bool)
+    for k, n in sizes.items():
+        inside[offs[k]:offs[k] + n] = True
+    assert bool((buf[~inside] == 0xA5).all()), "a guard band was written"
+    extra = G.tvd_tie_allowance(cfg, data) if kind == I.TVD else (G.akl_allowance(cfg, data) if kind == I.AKL else None)
+    G.check(dict(loss=loss, per_token_loss=ptl, grad_h_s=gh, grad_W_s=gW), G.run_oracle(cfg, data), "guarded call", extra)
