@@ -107,7 +107,8 @@ def akl_allowance(cfg, data, band2=8e-4, top2=2e-4):
     ddz = (m * dw / (n * cfg.tau))[:, None] * np.abs(g_f - g_r)
     return dict(per_token_loss=m * dw * np.abs(l_f - l_r), loss=float((m * dw * np.abs(l_f - l_r)).sum() / n),
                 grad_h_s=ddz @ np.abs(data["W_s"].astype(np.float64)),
-                grad_W_s=ddz.T @ np.abs(data["h_s"].astype(np.float64)), max_dw=float(dw.max()))
+                grad_W_s=ddz.T @ np.abs(data["h_s"].astype(np.float64)), max_dw=float(dw.max()),
+                mean_dw=float(dw.mean()))
 
 
 def check(out, ref, what="", extra_tol=None):
